@@ -1,0 +1,374 @@
+"""CPU oracle for the active-weight decode path (TEST INFRASTRUCTURE ONLY).
+
+This file is a plain, slow, fp64 NumPy statement of what the HIP library must
+compute.  It is the yardstick for parity tests, the smoke check and the
+`cpu_baseline` leg of the benchmark; the product path never imports it, and it
+imports nothing from the product.  It shares no code, tables or helpers with
+the HIP kernels.
+
+What it follows (ActiveFlow, arXiv 2504.08378):
+  * Section 2.1 ("Top-K sparsity"): for every linear operator only the input
+    activations of largest magnitude take part in the product; the paper states
+    the rule both as top-k and as "magnitude above a threshold" (Section 6,
+    "Caching", keeps one threshold per sparsity level) -> select_topk,
+    select_threshold.
+  * Section 4, pipeline operations T and C: T turns the activation into the
+    indices of the active weight channels; C computes the operator on those
+    channels only.  Because the result is exactly W (x * mask), the oracle
+    writes that definition out with the dense out-major matrix -> sparse_gemv.
+  * Section 3: the index set found at one layer is used for the same operator
+    of the next layers of its group (N = 4) -> decode_stack(reuse...), overlap.
+  * Section 6 ("Flash loading") and Section 7.1: weights are 4-bit with the
+    matrix transposed so that a channel read carries its scales -> the q4
+    functions (the quantiser itself is this build's own definition, see below).
+  * Fig. "simplified transformer layer" (Section 2.2): pre-norm block with
+    residual connections -> decode_layer.
+  * Eq. 9: sparsity sp is the fraction of channels dropped -> keep_count.
+
+Readings taken where the paper is silent: ties go to the lower channel index;
+index lists are ascending; the magnitude order is the integer order of the
+fp16 bit pattern with the sign cleared (so +0 == -0, Inf above finite, NaN
+above Inf); a threshold is strict (> t) and compared in fp32; one selection on
+a shared input serves q, k, v (and gate, up).  The 4-bit quantiser: groups of
+32 consecutive input channels per output row, scale s = fp16(max|w| / 7)
+(fp32 division), q = clamp(rint(w / s), -7, 7) (fp32 division, ties to even),
+s == 0 -> q = 0, stored nibble = q + 8, value = (nibble - 8) * s.
+
+All floating-point work is fp64 on the given fp16 bits; tensors that travel
+between operators are rounded to fp16 (ties to even) where the device stores
+fp16.  Pins for every function live in tests/test_oracle_*.py.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+SEL_TOPK = 0
+SEL_THRESHOLD = 1
+SEL_DENSE = 2
+
+# selection points of a decoder layer, in execution order
+P_QKV, P_O, P_GATEUP, P_DOWN = 0, 1, 2, 3
+POINT_NAMES = ("qkv", "o", "gateup", "down")
+
+
+# --------------------------------------------------------------------------
+# selection (Section 2.1; Section 4 operation T)
+# --------------------------------------------------------------------------
+def keep_count(n: int, sparsity_percent: int) -> int:
+    """k for a sparsity level: the paper's Eq. 9 counts (1 - sp) of the channels
+    as active; integer form k = n - floor(sp * n / 100)."""
+    return n - (int(sparsity_percent) * int(n)) // 100
+
+
+def magnitude_key(x) -> np.ndarray:
+    """Integer magnitude order of fp16 values: bit pattern with the sign cleared."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    return x.view(np.uint16) & np.uint16(0x7FFF)
+
+
+def select_topk(x, k: int) -> np.ndarray:
+    """The k channels of largest |x_j|, ties to the lower index, ascending int32."""
+    key = magnitude_key(x).astype(np.int64)
+    n = key.shape[0]
+    if not 0 <= k <= n:
+        raise ValueError("k out of range")
+    j = np.arange(n)
+    # primary key: magnitude descending; secondary: index ascending
+    order = np.lexsort((j, -key))
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def select_threshold(x, t: float) -> np.ndarray:
+    """{j : |x_j| > t}, compared in fp32 (fp16 -> fp32 is exact), ascending int32."""
+    mag = np.abs(np.asarray(x, dtype=np.float16).astype(np.float32))
+    return np.nonzero(mag > np.float32(t))[0].astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# sparse GEMV (Section 4 operation C) -- the dense definition W (x * mask)
+# --------------------------------------------------------------------------
+def _mask(n: int, idx) -> np.ndarray:
+    m = np.zeros(n, dtype=np.float64)
+    m[np.asarray(idx, dtype=np.int64)] = 1.0
+    return m
+
+
+def sparse_gemv(W, x, idx) -> np.ndarray:
+    """y = W (x * mask(idx)); W is the out-major [out][in] matrix; fp64 result."""
+    W = np.asarray(W)
+    xm = np.asarray(x).astype(np.float64) * _mask(W.shape[1], idx)
+    return W.astype(np.float64) @ xm
+
+
+def round_f16(v) -> np.ndarray:
+    """Round to fp16, ties to even (what a device store of an fp16 tensor does)."""
+    return np.asarray(v, dtype=np.float64).astype(np.float16)
+
+
+# --------------------------------------------------------------------------
+# 4-bit group quantisation (Section 6 "Flash loading", Section 7.1)
+# --------------------------------------------------------------------------
+Q4_GROUP = 32
+
+
+def quantize_q4_g32(W):
+    """W[out][in] fp16 -> (nib uint8 [out][in] in 1..15, scales fp16 [in/32][out])."""
+    W = np.asarray(W, dtype=np.float16)
+    out, n_in = W.shape
+    if n_in % Q4_GROUP:
+        raise ValueError("in must be a multiple of 32")
+    w32 = W.astype(np.float32).reshape(out, n_in // Q4_GROUP, Q4_GROUP)
+    amax = np.max(np.abs(w32), axis=2)                                    # exact
+    s16 = (amax / np.float32(7.0)).astype(np.float32).astype(np.float16)  # fp32 divide, then RNE
+    s32 = s16.astype(np.float32)[:, :, None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.rint((w32 / s32).astype(np.float32))
+    q = np.where(s32 == 0, np.float32(0), np.clip(r, -7, 7)).astype(np.int32)
+    nib = (q + 8).astype(np.uint8).reshape(out, n_in)
+    return nib, np.ascontiguousarray(s16.T)
+
+
+def pack_q4(nib) -> np.ndarray:
+    """Logical packed form [in][out/2]: byte i of row j = column 2i (low nibble) and 2i+1 (high)."""
+    nib = np.asarray(nib, dtype=np.uint8)
+    t = np.ascontiguousarray(nib.T)                    # [in][out]
+    return (t[:, 0::2] | (t[:, 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_q4(packed, out: int) -> np.ndarray:
+    """Inverse of pack_q4: [in][out/2] bytes -> nib [out][in]."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    t = np.empty((packed.shape[0], out), dtype=np.uint8)
+    t[:, 0::2] = packed & 0xF
+    t[:, 1::2] = packed >> 4
+    return np.ascontiguousarray(t.T)
+
+
+def dequant_q4_g32(nib, scales) -> np.ndarray:
+    """(nib - 8) * scale of the group the input channel falls in, fp64 [out][in]."""
+    nib = np.asarray(nib)
+    s = np.asarray(scales).astype(np.float64)          # [in/32][out]
+    q = nib.astype(np.float64) - 8.0
+    return q * np.repeat(s.T, Q4_GROUP, axis=1)
+
+
+def sparse_gemv_q4(nib, scales, x, idx) -> np.ndarray:
+    return sparse_gemv(dequant_q4_g32(nib, scales), x, idx)
+
+
+# --------------------------------------------------------------------------
+# small-batch union (each token keeps its own mask)
+# --------------------------------------------------------------------------
+def union_indices(idx_b) -> np.ndarray:
+    """Sorted union of the per-token index sets."""
+    if len(idx_b) == 0:
+        return np.zeros(0, dtype=np.int32)
+    return np.unique(np.concatenate([np.asarray(i, dtype=np.int32) for i in idx_b])).astype(np.int32)
+
+
+def union_gemv(W, X, idx_b) -> np.ndarray:
+    """Y[b] = W (X[b] * mask(idx_b[b])): B independent single-token products."""
+    return np.stack([sparse_gemv(W, X[b], idx_b[b]) for b in range(len(idx_b))])
+
+
+# --------------------------------------------------------------------------
+# cross-layer reuse metric (Section 3; Section 2.2 "Top-K precision")
+# --------------------------------------------------------------------------
+def overlap(reused, true_idx) -> float:
+    """|reused & true| / |true| (1.0 when the true set is empty)."""
+    t = np.asarray(true_idx)
+    if t.size == 0:
+        return 1.0
+    return float(np.intersect1d(np.asarray(reused), t).size) / float(t.size)
+
+
+# --------------------------------------------------------------------------
+# glue operators of the pre-norm LLaMA-style block (Fig. in Section 2.2)
+# --------------------------------------------------------------------------
+def rmsnorm(h, g, eps: float) -> np.ndarray:
+    h = np.asarray(h).astype(np.float64)
+    return h / np.sqrt(np.mean(h * h) + eps) * np.asarray(g).astype(np.float64)
+
+
+def rope(v, pos: int, theta: float) -> np.ndarray:
+    """Rotate-half rotary embedding of v[..., head_dim] at position pos."""
+    v = np.asarray(v, dtype=np.float64)
+    hd = v.shape[-1]
+    half = hd // 2
+    i = np.arange(half, dtype=np.float64)
+    ang = pos * theta ** (-2.0 * i / hd)
+    c, s = np.cos(ang), np.sin(ang)
+    a, b = v[..., :half], v[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def silu(v) -> np.ndarray:
+    v = np.asarray(v, dtype=np.float64)
+    return v / (1.0 + np.exp(-v))
+
+
+def attention_decode(q, K, V, n_keys: int) -> np.ndarray:
+    """softmax(q K^T / sqrt(hd)) V over the first n_keys cache slots.
+
+    q [n_heads][hd] fp64; K, V [n_kv][cap][hd]; query head h reads kv head
+    h // (n_heads / n_kv).  Returns [n_heads][hd] fp64.
+    """
+    n_heads, hd = q.shape
+    rep = n_heads // K.shape[0]
+    out = np.empty((n_heads, hd), dtype=np.float64)
+    for h in range(n_heads):
+        Kh = K[h // rep, :n_keys].astype(np.float64)
+        Vh = V[h // rep, :n_keys].astype(np.float64)
+        s = Kh @ q[h] / np.sqrt(float(hd))
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        out[h] = p @ Vh
+    return out
+
+
+@dataclass
+class LayerCfg:
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ffn: int
+    rms_eps: float = 1e-5
+    rope_theta: float = 10000.0
+
+
+@dataclass
+class SelectCfg:
+    """mode: SEL_TOPK (k per point), SEL_THRESHOLD (t per point) or SEL_DENSE.
+    reuse_mask bit p set -> do not select at point p, use the set handed in."""
+    mode: int = SEL_TOPK
+    k: tuple = (0, 0, 0, 0)
+    t: tuple = (0.0, 0.0, 0.0, 0.0)
+    reuse_mask: int = 0
+
+
+@dataclass
+class LayerTrace:
+    """Everything a parity test needs from one layer, stage by stage."""
+    x: list = field(default_factory=lambda: [None] * 4)     # fp16 input of each selection point
+    idx: list = field(default_factory=lambda: [None] * 4)   # int32 index set used at each point
+    qkv: np.ndarray = None          # fp16 [qkv_out] (before rope)
+    attn: np.ndarray = None         # fp16 [n_heads*hd]
+    h_mid: np.ndarray = None        # fp16 [d] after the attention block
+    gateup: np.ndarray = None       # fp16 [2*ffn]
+    hidden: np.ndarray = None       # fp16 [d] layer output
+    k_new: np.ndarray = None        # fp16 [n_kv][hd] appended key (rotated)
+    v_new: np.ndarray = None        # fp16 [n_kv][hd]
+
+
+def _select(x16, p: int, sel: SelectCfg, given):
+    n = x16.shape[0]
+    if sel.reuse_mask >> p & 1:
+        return np.asarray(given[p], dtype=np.int32)
+    if sel.mode == SEL_TOPK:
+        return select_topk(x16, sel.k[p])
+    if sel.mode == SEL_THRESHOLD:
+        return select_threshold(x16, sel.t[p])
+    return np.arange(n, dtype=np.int32)
+
+
+def _linear(W, x16, idx, weights_q4):
+    if weights_q4:
+        nib, s = W
+        return sparse_gemv_q4(nib, s, x16, idx)
+    return sparse_gemv(W, x16, idx)
+
+
+def decode_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
+                 sel: SelectCfg, sets=None, weights_q4: bool = False) -> LayerTrace:
+    """One batch-1 decode step of a pre-norm block with activation sparsity at the
+    inputs of qkv, o, gate/up and down.
+
+    w holds out-major matrices Wq, Wk, Wv, Wo, Wgate, Wup, Wdown (fp16, or
+    (nib, scales) pairs when weights_q4) and gains g_attn, g_ffn.  K, V
+    [n_kv][cap][hd] fp16 are updated in place at slot kv_len.  `sets` gives the
+    index sets for points whose reuse bit is set.  Returns the stage trace.
+    """
+    tr = LayerTrace()
+    h0 = np.asarray(hidden, dtype=np.float16)
+    nh, nkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+
+    # attention block
+    x0 = round_f16(rmsnorm(h0, w["g_attn"], cfg.rms_eps))
+    i0 = _select(x0, P_QKV, sel, sets)
+    q = _linear(w["Wq"], x0, i0, weights_q4)
+    k = _linear(w["Wk"], x0, i0, weights_q4)
+    v = _linear(w["Wv"], x0, i0, weights_q4)
+    qkv16 = round_f16(np.concatenate([q, k, v]))
+    q16 = qkv16[: nh * hd].reshape(nh, hd)
+    k16 = qkv16[nh * hd: (nh + nkv) * hd].reshape(nkv, hd)
+    v16 = qkv16[(nh + nkv) * hd:].reshape(nkv, hd)
+    qr = rope(q16, pos, cfg.rope_theta)
+    k_new = round_f16(rope(k16, pos, cfg.rope_theta))
+    K[:, kv_len, :] = k_new
+    V[:, kv_len, :] = v16
+    a16 = round_f16(attention_decode(qr, K, V, kv_len + 1).reshape(-1))
+    i1 = _select(a16, P_O, sel, sets)
+    h1 = round_f16(h0.astype(np.float64) + _linear(w["Wo"], a16, i1, weights_q4))
+
+    # feed-forward block
+    x2 = round_f16(rmsnorm(h1, w["g_ffn"], cfg.rms_eps))
+    i2 = _select(x2, P_GATEUP, sel, sets)
+    g = _linear(w["Wgate"], x2, i2, weights_q4)
+    u = _linear(w["Wup"], x2, i2, weights_q4)
+    gu16 = round_f16(np.concatenate([g, u]))
+    f = cfg.d_ffn
+    x3 = round_f16(silu(gu16[:f]) * gu16[f:].astype(np.float64))
+    i3 = _select(x3, P_DOWN, sel, sets)
+    h2 = round_f16(h1.astype(np.float64) + _linear(w["Wdown"], x3, i3, weights_q4))
+
+    tr.x = [x0, a16, x2, x3]
+    tr.idx = [i0, i1, i2, i3]
+    tr.qkv, tr.attn, tr.h_mid, tr.gateup, tr.hidden = qkv16, a16, h1, gu16, h2
+    tr.k_new, tr.v_new = k_new, v16.copy()
+    return tr
+
+
+def decode_stack(cfg: LayerCfg, layers: list, hidden, Ks: list, Vs: list, kv_len: int, pos: int,
+                 sel: SelectCfg, group: int = 1, reuse_points: int = 0, weights_q4: bool = False,
+                 want_overlap: bool = False):
+    """Run the layers in order.  With group > 1 (Section 3, N = 4 in the paper) layer
+    l with l % group == 0 selects; the other layers of its group reuse its sets at
+    the points whose bit is set in reuse_points.  Returns (traces, overlap) where
+    overlap[l][p] compares the set used with the set the layer's own input would
+    have selected (None for points that selected themselves or when not wanted)."""
+    traces, ov = [], []
+    sets = [None] * 4
+    h = hidden
+    for l, w in enumerate(layers):
+        follower = group > 1 and (l % group) != 0
+        mask = sel.reuse_mask | (reuse_points if follower else 0)
+        s = SelectCfg(sel.mode, sel.k, sel.t, mask)
+        tr = decode_layer(cfg, w, h, Ks[l], Vs[l], kv_len, pos, s, sets, weights_q4)
+        row = [None] * 4
+        if want_overlap:
+            own = SelectCfg(sel.mode, sel.k, sel.t, 0)
+            for p in range(4):
+                if mask >> p & 1:
+                    row[p] = overlap(tr.idx[p], _select(tr.x[p], p, own, None))
+        if not follower:
+            sets = list(tr.idx)
+        traces.append(tr)
+        ov.append(row)
+        h = tr.hidden
+    return traces, ov
+
+
+def rel_err(got, ref) -> float:
+    """Output error measure used by the parity tests:
+    max_i |got_i - ref_i| / max(|ref_i|, 0.01 * rms(ref))."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    if ref.size == 0:
+        return 0.0
+    floor = 0.01 * np.sqrt(np.mean(ref * ref))
+    den = np.maximum(np.abs(ref), floor)
+    den = np.where(den == 0, 1.0, den)
+    return float(np.max(np.abs(got - ref) / den))
