@@ -1,0 +1,196 @@
+/*
+ * activeflow.h -- C ABI of the MI355X (gfx950) active-weight decode library.
+ *
+ * The library implements the compute half of ActiveFlow's active-weight
+ * inference (arXiv 2504.08378) for batch-1 decode on one GPU:
+ *   T  (Section 4, "Top-K"):     activation -> indices of the active input channels
+ *   C  (Section 4, "Computing"): the linear operator over those channels only
+ *   Section 3: the index set of one layer reused by the next layers of its group
+ * Weights are stored input-channel-major (Section 6, "Flash loading": the
+ * matrix is transposed so that reading one channel returns everything that
+ * channel needs), so an active channel is one contiguous row in HBM.
+ *
+ * Conventions (all entry points)
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless the
+ *     argument comment says "host".  The library never frees caller memory
+ *     and allocates no device memory of its own; scratch comes from the
+ *     caller through af_set_workspace().
+ *   - Every call only enqueues work on the context's HIP stream (borrowed from
+ *     the caller) and returns; nothing synchronises.  Results are valid once
+ *     the caller has synchronised that stream.  Calls on one context must not
+ *     overlap on different streams: they share the workspace.
+ *   - Return value: AF_OK (0) or a negative af_status.  All argument checks
+ *     happen on the host before anything is launched; a failing call has
+ *     launched nothing.  af_strerror() names a code.
+ *   - fp16 tensors are IEEE binary16; index lists are int32, ascending, unique.
+ *   - "in-major" matrix: Wt[in][ld] fp16, row j holds the weights of input
+ *     channel j for all outputs (ld >= out, ld % 8 == 0, out % 8 == 0).
+ */
+#ifndef ACTIVEFLOW_H
+#define ACTIVEFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AF_OK = 0,
+  AF_EINVAL = -1,     /* a scalar argument is out of range                    */
+  AF_ENULL = -2,      /* a required pointer is NULL                           */
+  AF_ESHAPE = -3,     /* a dimension violates the layout rules stated below   */
+  AF_EWORKSPACE = -4, /* no workspace set, or it is too small for this call   */
+  AF_EHIP = -5        /* the HIP runtime reported an error (launch, stream)   */
+} af_status;
+
+enum { AF_F16 = 0, AF_F32 = 1 };                              /* y_kind            */
+enum { AF_W_F16 = 0, AF_W_Q4G32 = 1 };                        /* weight_kind       */
+enum { AF_SEL_TOPK = 0, AF_SEL_THRESHOLD = 1, AF_SEL_DENSE = 2 }; /* selection mode */
+enum { AF_MAX_N = 32768, AF_MAX_BATCH = 8 };
+
+typedef struct af_ctx af_ctx; /* opaque */
+
+/* Context. `device` is the HIP device ordinal, `hip_stream` a hipStream_t (may be 0 for
+ * the default stream); the stream is borrowed, never destroyed. */
+int af_create(af_ctx** out, int device, void* hip_stream);
+int af_destroy(af_ctx* ctx);
+int af_set_stream(af_ctx* ctx, void* hip_stream);
+const char* af_strerror(int status);
+
+/* Scratch memory.  af_workspace_bytes() gives the size that serves every call whose
+ * dimensions stay within max_in input channels, max_out output columns (of the widest
+ * fused matrix) and max_batch tokens; 0 if an argument is invalid.
+ * af_set_workspace() hands the buffer over for those limits (256-byte aligned, at least
+ * af_workspace_bytes() long; the caller keeps ownership and must keep it alive while the
+ * context uses it) and enqueues the clearing of its counter area on the stream.  Later
+ * calls whose dimensions exceed the limits return AF_EWORKSPACE. */
+size_t af_workspace_bytes(int max_in, int max_out, int max_batch);
+int af_set_workspace(af_ctx* ctx, void* dev_ptr, size_t bytes, int max_in, int max_out,
+                     int max_batch);
+
+/* ---- selection: Section 2.1 (Top-K sparsity) and Section 4, operation T ----------------
+ * af_select_topk: idx[0..k) = the k channels of largest |x_j|, ascending.  Magnitude order
+ *   is the integer order of the fp16 bits with the sign cleared (+0 == -0, Inf above all
+ *   finite values, NaN above Inf); equal magnitudes go to the lower index.
+ *   x fp16 [n], 0 <= k <= n <= AF_MAX_N.  k == 0 writes nothing.
+ * af_select_threshold: idx = { j : |x_j| > t } (strict, compared in fp32, NaN never
+ *   passes), ascending; *count receives the number written.  idx must hold n entries.
+ *   This is the form the paper's own index kernel takes (Section 6, "Caching": one
+ *   preloaded threshold per sparsity level). */
+int af_select_topk(af_ctx* ctx, const void* x_f16, int n, int k, int32_t* idx);
+int af_select_threshold(af_ctx* ctx, const void* x_f16, int n, float t, int32_t* idx,
+                        int32_t* count);
+
+/* ---- weight layout: Section 6 "Flash loading" (channel-major storage) -------------------
+ * af_pack_inmajor_f16: W[out][in] fp16 (row-major, out-major) -> Wt[in][ld] at column
+ *   offset col0 (so several operators that share an input can be fused side by side:
+ *   q|k|v and gate|up).  Columns outside [col0, col0+out) are left untouched.
+ * af_pack_q4_g32: quantise W[out][in] fp16 to 4 bits in groups of 32 consecutive input
+ *   channels per output: s = fp16(max|w| / 7), q = clamp(rint(w / s), -7, 7) (fp32
+ *   arithmetic, ties to even, s == 0 -> q = 0), nibble = q + 8.
+ *   packed u8 [in][ld/2]: byte i of row j = columns 2i (low nibble) and 2i+1 (high);
+ *   scales fp16 [in/32][ld].  in % 32 == 0, out % 8 == 0, col0 % 8 == 0, ld % 8 == 0. */
+int af_pack_inmajor_f16(af_ctx* ctx, const void* W_f16, int out, int in, void* Wt, int ld,
+                        int col0);
+int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
+                   void* scales_f16, int ld, int col0);
+
+/* ---- sparse GEMV: Section 4, operation C -----------------------------------------------
+ * y[o] = sum over t < nidx of Wt[idx[t]][o] * x[idx[t]]  (+ residual[o] if given),
+ * fp32 accumulation, o in [0, out).  Only the rows named by idx are read.
+ *   idx == NULL means all channels 0..in-1 (dense).  Otherwise idx holds nidx entries
+ *   (ascending, unique, in [0, in) -- a precondition, not checked); nidx is *nidx_dev if
+ *   nidx_dev != NULL (a device int32 written by af_select_threshold, must be <= nidx_host)
+ *   else nidx_host.  nidx == 0 gives y = residual (or 0).
+ *   y: fp16 or fp32 [out] by y_kind; residual: fp16 [out] or NULL; y may alias residual.
+ * The result is deterministic: partial sums are combined in a fixed order.
+ * af_sparse_gemv_q4: same with W = (nibble - 8) * scale of the row's group (layout of
+ *   af_pack_q4_g32). */
+int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, const void* x_f16,
+                       const int32_t* idx, int nidx_host, const int32_t* nidx_dev, void* y,
+                       int y_kind, const void* residual_f16);
+int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, int in, int out,
+                      int ld, const void* x_f16, const int32_t* idx, int nidx_host,
+                      const int32_t* nidx_dev, void* y, int y_kind, const void* residual_f16);
+
+/* ---- small-batch union GEMV (extension of operation C to B tokens) ----------------------
+ * Each of the B <= AF_MAX_BATCH tokens has its own index set idx_b[b][0..k); the kernel
+ * reads every row of the union once and applies each token's mask:
+ *   Y[b][o] = sum over j in idx_b[b] of Wt[j][o] * X[b][j].
+ * X fp16 [B][in]; idx_b int32 [B][k]; union_idx int32 [in] and union_n int32 [1] receive
+ * the ascending union and its size; Y [B][out] fp16 or fp32. */
+int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                             const void* X_f16, int B, const int32_t* idx_b, int k,
+                             int32_t* union_idx, int32_t* union_n, void* Y, int y_kind);
+
+/* ---- decoder layer: block of Fig. "simplified transformer layer" (Section 2.2) with
+ * operations T and C at the inputs of qkv, o, gate/up and down ---------------------------- */
+typedef struct {
+  int d_model, n_heads, n_kv_heads, head_dim, d_ffn; /* head_dim must be 128 or 64 */
+  float rms_eps, rope_theta;
+  int weight_kind; /* AF_W_F16 | AF_W_Q4G32 */
+} af_layer_cfg;
+
+/* In-major, fused: Wqkv [d][(h+2kv)*hd] (q|k|v), Wo [h*hd][d], Wgateup [d][2*ffn]
+ * (gate|up), Wdown [ffn][d]; leading dimension == number of columns.  For AF_W_Q4G32 the
+ * W* pointers are packed nibbles and S* their scales; S* are NULL for fp16 weights.
+ * g_*: fp16 [d] RMSNorm gains. */
+typedef struct {
+  const void *Wqkv, *Wo, *Wgateup, *Wdown;
+  const void *Sqkv, *So, *Sgateup, *Sdown;
+  const void *g_attn_norm, *g_ffn_norm;
+} af_layer_weights;
+
+/* Index sets of the four selection points (0 qkv, 1 o, 2 gate/up, 3 down).  idx[p] holds
+ * n_p entries (n_p = input width of the point), count[p] one int32; both device memory.
+ * A point that selects writes them; a point whose reuse bit is set reads them. */
+typedef struct {
+  int32_t* idx[4];
+  int32_t* count[4];
+} af_idx_sets;
+
+typedef struct {
+  int mode;            /* AF_SEL_TOPK | AF_SEL_THRESHOLD | AF_SEL_DENSE */
+  int k[4];            /* top-k mode: channels kept at each point        */
+  float t[4];          /* threshold mode: threshold at each point        */
+  unsigned reuse_mask; /* bit p set: do not select at p, use sets (Section 3) */
+} af_select_cfg;
+
+/* One batch-1 decode step of one layer.  hidden_in/hidden_out fp16 [d] (may alias).
+ * k_cache/v_cache fp16 [n_kv][kv_cap][hd]; the new (rotated) key and the value are
+ * written at slot kv_len (< kv_cap) and attention runs over slots 0..kv_len; `pos` is
+ * the rotary position.  Inter-operator tensors are fp16. */
+int af_decode_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
+                    const void* hidden_in, void* hidden_out, void* k_cache, void* v_cache,
+                    int kv_len, int kv_cap, int pos, const af_select_cfg* sel,
+                    af_idx_sets* sets);
+
+/* n_layers layers in sequence.  w, k_caches, v_caches, sets: host arrays of n_layers
+ * entries.  With group > 1, layer l with l % group != 0 reuses the sets of its group's
+ * first layer at the points named by reuse_points (Section 3, N = 4); sets[l] of a
+ * follower is not touched at those points.  sel->reuse_mask applies to every layer. */
+int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w, int n_layers,
+                    const void* hidden_in, void* hidden_out, void* const* k_caches,
+                    void* const* v_caches, int kv_len, int kv_cap, int pos,
+                    const af_select_cfg* sel, int group, unsigned reuse_points,
+                    af_idx_sets* sets);
+
+/* Device address of an inter-operator tensor of the most recent af_decode_layer call on
+ * this context (for tests): which = 0 x_qkv [d], 1 qkv [(h+2kv)*hd], 2 attn [h*hd],
+ * 3 h_mid [d], 4 x_gateup [d], 5 gateup [2*ffn], 6 x_down [ffn].  fp16. */
+int af_layer_tap(af_ctx* ctx, int which, const void** dev_ptr);
+
+/* Stream capture helpers: record the calls made between begin and end into a HIP graph
+ * and replay it.  The graph holds the pointers and scalars of the recorded calls. */
+typedef struct af_graph af_graph;
+int af_capture_begin(af_ctx* ctx);
+int af_capture_end(af_ctx* ctx, af_graph** out);
+int af_graph_launch(af_ctx* ctx, af_graph* g);
+int af_graph_destroy(af_graph* g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACTIVEFLOW_H */

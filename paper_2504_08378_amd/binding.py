@@ -1,0 +1,295 @@
+"""ctypes binding of include/activeflow.h: argument marshalling only.
+
+Every function here takes torch CUDA tensors (used purely as device buffers), checks
+dtype/contiguity, passes raw device pointers to the C ABI and raises AfError on a non-zero
+status.  No arithmetic of the method happens in Python.  There is no CPU fallback: if the
+shared library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libactiveflow.so")
+
+AF_F16, AF_F32 = 0, 1
+AF_W_F16, AF_W_Q4G32 = 0, 1
+AF_SEL_TOPK, AF_SEL_THRESHOLD, AF_SEL_DENSE = 0, 1, 2
+AF_MAX_N, AF_MAX_BATCH = 32768, 8
+
+EXPORTS = [
+    "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
+    "af_set_workspace", "af_select_topk", "af_select_threshold", "af_pack_inmajor_f16",
+    "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_sparse_gemv_union_f16",
+    "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
+    "af_graph_launch", "af_graph_destroy",
+]
+
+
+class AfError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({strerror(status)})")
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("d_model", C.c_int), ("n_heads", C.c_int), ("n_kv_heads", C.c_int),
+                ("head_dim", C.c_int), ("d_ffn", C.c_int), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float), ("weight_kind", C.c_int)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("Wqkv", "Wo", "Wgateup", "Wdown", "Sqkv", "So", "Sgateup", "Sdown",
+                 "g_attn_norm", "g_ffn_norm")]
+
+
+class IdxSets(C.Structure):
+    _fields_ = [("idx", C.c_void_p * 4), ("count", C.c_void_p * 4)]
+
+
+class SelectCfg(C.Structure):
+    _fields_ = [("mode", C.c_int), ("k", C.c_int * 4), ("t", C.c_float * 4),
+                ("reuse_mask", C.c_uint)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libactiveflow.so (built in-tree by paper_2504_08378_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2504_08378_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i, f, u, sz = C.c_void_p, C.c_int, C.c_float, C.c_uint, C.c_size_t
+    sig = {
+        "af_create": (i, [C.POINTER(vp), i, vp]),
+        "af_destroy": (i, [vp]),
+        "af_set_stream": (i, [vp, vp]),
+        "af_strerror": (C.c_char_p, [i]),
+        "af_workspace_bytes": (sz, [i, i, i]),
+        "af_set_workspace": (i, [vp, vp, sz, i, i, i]),
+        "af_select_topk": (i, [vp, vp, i, i, vp]),
+        "af_select_threshold": (i, [vp, vp, i, f, vp, vp]),
+        "af_pack_inmajor_f16": (i, [vp, vp, i, i, vp, i, i]),
+        "af_pack_q4_g32": (i, [vp, vp, i, i, vp, vp, i, i]),
+        "af_sparse_gemv_f16": (i, [vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_sparse_gemv_q4": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_sparse_gemv_union_f16": (i, [vp, vp, i, i, i, vp, i, vp, i, vp, vp, vp, i]),
+        "af_decode_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, vp,
+                                i, i, i, C.POINTER(SelectCfg), C.POINTER(IdxSets)]),
+        "af_decode_stack": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), i, vp, vp,
+                                C.POINTER(vp), C.POINTER(vp), i, i, i, C.POINTER(SelectCfg), i, u,
+                                C.POINTER(IdxSets)]),
+        "af_layer_tap": (i, [vp, i, C.POINTER(vp)]),
+        "af_capture_begin": (i, [vp]),
+        "af_capture_end": (i, [vp, C.POINTER(vp)]),
+        "af_graph_launch": (i, [vp, vp]),
+        "af_graph_destroy": (i, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return lib().af_strerror(status).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise AfError(status, what)
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """One af_ctx bound to a device and a torch stream, with its workspace tensor."""
+
+    def __init__(self, device: int = 0, stream: torch.cuda.Stream | None = None,
+                 max_in: int = AF_MAX_N, max_out: int = 65536, max_batch: int = AF_MAX_BATCH):
+        L = lib()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the active-weight path has no CPU fallback")
+        self.device = torch.device("cuda", device)
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        h = C.c_void_p()
+        _check(L.af_create(C.byref(h), device, C.c_void_p(self.stream.cuda_stream)), "af_create")
+        self._h = h
+        nbytes = L.af_workspace_bytes(max_in, max_out, max_batch)
+        if nbytes == 0:
+            raise ValueError("invalid workspace limits")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        _check(L.af_set_workspace(h, _ptr(self.workspace), nbytes, max_in, max_out, max_batch),
+               "af_set_workspace")
+        self.max_in, self.max_out, self.max_batch = max_in, max_out, max_batch
+
+    def close(self):
+        if getattr(self, "_h", None) is not None:
+            self.synchronize()
+            lib().af_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def synchronize(self):
+        self.stream.synchronize()
+
+    # ---- selection -------------------------------------------------------------------
+    def select_topk(self, x, k: int, idx=None):
+        n = x.numel()
+        if idx is None:
+            idx = torch.empty(max(k, 1), dtype=torch.int32, device=self.device)
+        _check(lib().af_select_topk(self._h, _ptr(x, torch.float16, "x"), n, k,
+                                    _ptr(idx, torch.int32, "idx")), "af_select_topk")
+        return idx[:k]
+
+    def select_threshold(self, x, t: float, idx=None, count=None):
+        n = x.numel()
+        if idx is None:
+            idx = torch.empty(max(n, 1), dtype=torch.int32, device=self.device)
+        if count is None:
+            count = torch.empty(1, dtype=torch.int32, device=self.device)
+        _check(lib().af_select_threshold(self._h, _ptr(x, torch.float16, "x"), n, float(t),
+                                         _ptr(idx, torch.int32, "idx"),
+                                         _ptr(count, torch.int32, "count")), "af_select_threshold")
+        return idx, count
+
+    # ---- packing ---------------------------------------------------------------------
+    def pack_inmajor_f16(self, W, Wt=None, ld=None, col0=0):
+        out, n_in = W.shape
+        if Wt is None:
+            ld = out if ld is None else ld
+            Wt = torch.empty((n_in, ld), dtype=torch.float16, device=self.device)
+        ld = Wt.shape[1]
+        _check(lib().af_pack_inmajor_f16(self._h, _ptr(W, torch.float16, "W"), out, n_in,
+                                         _ptr(Wt, torch.float16, "Wt"), ld, col0),
+               "af_pack_inmajor_f16")
+        return Wt
+
+    def pack_q4_g32(self, W, packed=None, scales=None, ld=None, col0=0):
+        out, n_in = W.shape
+        if packed is None:
+            ld = out if ld is None else ld
+            packed = torch.empty((n_in, ld // 2), dtype=torch.uint8, device=self.device)
+            scales = torch.empty((n_in // 32, ld), dtype=torch.float16, device=self.device)
+        ld = scales.shape[1]
+        _check(lib().af_pack_q4_g32(self._h, _ptr(W, torch.float16, "W"), out, n_in,
+                                    _ptr(packed, torch.uint8, "packed"),
+                                    _ptr(scales, torch.float16, "scales"), ld, col0),
+               "af_pack_q4_g32")
+        return packed, scales
+
+    # ---- GEMV ------------------------------------------------------------------------
+    def sparse_gemv_f16(self, Wt, x, idx=None, nidx=None, nidx_dev=None, y=None, y_kind=AF_F16,
+                        residual=None, out=None):
+        n_in, ld = Wt.shape
+        out = ld if out is None else out
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        if idx is not None and nidx is None:
+            nidx = idx.numel()
+        _check(lib().af_sparse_gemv_f16(
+            self._h, _ptr(Wt, torch.float16, "Wt"), n_in, out, ld, _ptr(x, torch.float16, "x"),
+            _ptr(idx, torch.int32, "idx"), int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"),
+            _ptr(y, None, "y"), y_kind, _ptr(residual, torch.float16, "residual")),
+            "af_sparse_gemv_f16")
+        return y
+
+    def sparse_gemv_q4(self, packed, scales, x, idx=None, nidx=None, nidx_dev=None, y=None,
+                       y_kind=AF_F16, residual=None, out=None):
+        n_in = packed.shape[0]
+        ld = scales.shape[1]
+        out = ld if out is None else out
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        if idx is not None and nidx is None:
+            nidx = idx.numel()
+        _check(lib().af_sparse_gemv_q4(
+            self._h, _ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float16, "scales"),
+            n_in, out, ld, _ptr(x, torch.float16, "x"), _ptr(idx, torch.int32, "idx"),
+            int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"), _ptr(y, None, "y"), y_kind,
+            _ptr(residual, torch.float16, "residual")), "af_sparse_gemv_q4")
+        return y
+
+    def sparse_gemv_union_f16(self, Wt, X, idx_b, y_kind=AF_F16, out=None):
+        n_in, ld = Wt.shape
+        out = ld if out is None else out
+        B, k = idx_b.shape
+        Y = torch.empty((B, out), dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                        device=self.device)
+        union_idx = torch.empty(n_in, dtype=torch.int32, device=self.device)
+        union_n = torch.empty(1, dtype=torch.int32, device=self.device)
+        _check(lib().af_sparse_gemv_union_f16(
+            self._h, _ptr(Wt, torch.float16, "Wt"), n_in, out, ld, _ptr(X, torch.float16, "X"), B,
+            _ptr(idx_b, torch.int32, "idx_b"), k, _ptr(union_idx, torch.int32, "union_idx"),
+            _ptr(union_n, torch.int32, "union_n"), _ptr(Y, None, "Y"), y_kind),
+            "af_sparse_gemv_union_f16")
+        return Y, union_idx, union_n
+
+    # ---- layer / stack ---------------------------------------------------------------
+    def decode_layer(self, cfg: LayerCfg, w: LayerWeights, hidden_in, hidden_out, k_cache, v_cache,
+                     kv_len: int, kv_cap: int, pos: int, sel: SelectCfg, sets: IdxSets | None):
+        _check(lib().af_decode_layer(
+            self._h, C.byref(cfg), C.byref(w), _ptr(hidden_in, torch.float16, "hidden_in"),
+            _ptr(hidden_out, torch.float16, "hidden_out"), _ptr(k_cache, torch.float16, "k_cache"),
+            _ptr(v_cache, torch.float16, "v_cache"), kv_len, kv_cap, pos, C.byref(sel),
+            C.byref(sets) if sets is not None else None), "af_decode_layer")
+
+    def decode_stack(self, cfg: LayerCfg, w_array, n_layers: int, hidden_in, hidden_out,
+                     k_ptrs, v_ptrs, kv_len: int, kv_cap: int, pos: int, sel: SelectCfg,
+                     group: int, reuse_points: int, sets_array):
+        _check(lib().af_decode_stack(
+            self._h, C.byref(cfg), w_array, n_layers, _ptr(hidden_in, torch.float16, "hidden_in"),
+            _ptr(hidden_out, torch.float16, "hidden_out"), k_ptrs, v_ptrs, kv_len, kv_cap, pos,
+            C.byref(sel), group, reuse_points, sets_array), "af_decode_stack")
+
+    def layer_tap(self, which: int, n: int):
+        """fp16 view (a copy) of an inter-operator tensor of the last decode_layer call."""
+        p = C.c_void_p()
+        _check(lib().af_layer_tap(self._h, which, C.byref(p)), "af_layer_tap")
+        base = self.workspace.data_ptr()
+        off = p.value - base
+        return self.workspace[off: off + 2 * n].view(torch.float16).clone()
+
+    # ---- graphs ----------------------------------------------------------------------
+    def capture_begin(self):
+        _check(lib().af_capture_begin(self._h), "af_capture_begin")
+
+    def capture_end(self):
+        g = C.c_void_p()
+        _check(lib().af_capture_end(self._h, C.byref(g)), "af_capture_end")
+        return g
+
+    def graph_launch(self, g):
+        _check(lib().af_graph_launch(self._h, g), "af_graph_launch")
+
+    def graph_destroy(self, g):
+        _check(lib().af_graph_destroy(g), "af_graph_destroy")

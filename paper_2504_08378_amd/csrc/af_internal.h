@@ -1,0 +1,87 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "activeflow.h"
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+#define AF_WAVE 64
+
+// Workspace carve-up (byte offsets from the caller's buffer), fixed by the limits given to
+// af_set_workspace.
+struct af_ws_layout {
+  size_t tickets;       // int32[AF_N_TICKETS], zero between kernels
+  size_t partials;      // float[partial_floats]: split partial sums of the GEMVs
+  size_t attn_part;     // float[attn_floats]: per-(head, key split) softmax partials
+  size_t act[7];        // fp16 inter-operator tensors of a layer (see af_layer_tap)
+  size_t union_x;       // fp16 [max_in][8]: masked, transposed token values of the union GEMV
+  size_t union_flag;    // int32 [max_in]
+  size_t total;
+  size_t partial_floats;
+  size_t attn_floats;
+};
+enum { AF_N_TICKETS = 8192, AF_TICKET_ATTN = 4096 /* first ticket used by attention */ };
+
+af_ws_layout af_layout(int max_in, int max_out, int max_batch);
+
+struct af_ctx {
+  int device;
+  hipStream_t stream;
+  char* ws;
+  size_t ws_bytes;
+  int max_in, max_out, max_batch;
+  af_ws_layout lay;
+  int n_cu;
+};
+
+struct af_graph {
+  hipGraph_t graph;
+  hipGraphExec_t exec;
+};
+
+static inline int af_hip(hipError_t e) { return e == hipSuccess ? AF_OK : AF_EHIP; }
+#define AF_LAUNCH_CHECK()                          \
+  do {                                             \
+    if (hipGetLastError() != hipSuccess) return AF_EHIP; \
+  } while (0)
+
+// ---- internal launchers (host) -----------------------------------------------------------
+// Selection over an fp16 vector with an optional fused producer:
+//   AF_PRO_NONE    x = src
+//   AF_PRO_RMSNORM x = fp16(src * rsqrt(mean(src^2) + eps) * gain); x is also stored to x_out
+//   AF_PRO_SILUMUL x = fp16(silu(src[j]) * src[n + j]);             x is also stored to x_out
+enum { AF_PRO_NONE = 0, AF_PRO_RMSNORM = 1, AF_PRO_SILUMUL = 2 };
+struct af_select_args {
+  const half_t* src;
+  const half_t* gain;  // rmsnorm only
+  half_t* x_out;       // producer output (may be null for AF_PRO_NONE)
+  int n;
+  float eps;
+  int mode;            // AF_SEL_TOPK | AF_SEL_THRESHOLD | AF_SEL_DENSE (producer only)
+  int k;
+  float t;
+  int32_t* idx;
+  int32_t* count;      // may be null
+};
+int af_launch_select(af_ctx* ctx, int producer, const af_select_args& a);
+
+struct af_gemv_args {
+  const void* W;          // fp16 in-major, or packed nibbles
+  const half_t* scales;   // q4 only
+  int in, out, ld;
+  const half_t* x;
+  const int32_t* idx;     // null = dense
+  int nidx_host;
+  const int32_t* nidx_dev;
+  void* y;
+  int y_kind;
+  const half_t* residual;
+};
+int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
+int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);
+
+static inline size_t af_align(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }

@@ -1,0 +1,211 @@
+// Context, workspace, weight packing and graph helpers of the C ABI.
+#include <stdlib.h>
+#include <string.h>
+
+#include "af_internal.h"
+
+af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
+  af_ws_layout L{};
+  size_t off = 0;
+  L.tickets = off;
+  off = af_align(off + sizeof(int) * AF_N_TICKETS);
+  // split partials: S * out_pad floats per launch; the launchers shrink S to fit.
+  L.partial_floats = (size_t)(1u << 20) + (size_t)4 * max_out * max_batch;
+  L.partials = off;
+  off = af_align(off + L.partial_floats * sizeof(float));
+  L.attn_floats = (size_t)(1u << 18);
+  L.attn_part = off;
+  off = af_align(off + L.attn_floats * sizeof(float));
+  const size_t act_halves = (size_t)(max_in > max_out ? max_in : max_out);
+  for (int i = 0; i < 7; ++i) {
+    L.act[i] = off;
+    off = af_align(off + act_halves * sizeof(half_t));
+  }
+  L.union_x = off;
+  off = af_align(off + (size_t)max_in * 8 * sizeof(half_t));
+  L.union_flag = off;
+  off = af_align(off + (size_t)max_in * sizeof(int));
+  L.total = off;
+  return L;
+}
+
+extern "C" size_t af_workspace_bytes(int max_in, int max_out, int max_batch) {
+  if (max_in <= 0 || max_out <= 0 || max_batch <= 0) return 0;
+  if (max_in > AF_MAX_N || max_batch > AF_MAX_BATCH) return 0;
+  return af_layout(max_in, max_out, max_batch).total;
+}
+
+extern "C" int af_create(af_ctx** out, int device, void* hip_stream) {
+  if (!out) return AF_ENULL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return AF_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return AF_EHIP;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return AF_EHIP;
+  af_ctx* c = (af_ctx*)calloc(1, sizeof(af_ctx));
+  if (!c) return AF_EINVAL;
+  c->device = device;
+  c->stream = (hipStream_t)hip_stream;
+  c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  *out = c;
+  return AF_OK;
+}
+
+extern "C" int af_destroy(af_ctx* ctx) {
+  if (!ctx) return AF_ENULL;
+  free(ctx);
+  return AF_OK;
+}
+
+extern "C" int af_set_stream(af_ctx* ctx, void* hip_stream) {
+  if (!ctx) return AF_ENULL;
+  ctx->stream = (hipStream_t)hip_stream;
+  return AF_OK;
+}
+
+extern "C" const char* af_strerror(int status) {
+  switch (status) {
+    case AF_OK: return "ok";
+    case AF_EINVAL: return "argument out of range";
+    case AF_ENULL: return "required pointer is null";
+    case AF_ESHAPE: return "dimension violates the layout rules";
+    case AF_EWORKSPACE: return "workspace missing or too small";
+    case AF_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+__global__ void fill_int_kernel(int* p, int n, int v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+extern "C" int af_set_workspace(af_ctx* ctx, void* dev_ptr, size_t bytes, int max_in, int max_out,
+                                int max_batch) {
+  if (!ctx || !dev_ptr) return AF_ENULL;
+  const size_t need = af_workspace_bytes(max_in, max_out, max_batch);
+  if (need == 0) return AF_EINVAL;
+  if (bytes < need || ((uintptr_t)dev_ptr & 255u)) return AF_EWORKSPACE;
+  ctx->ws = (char*)dev_ptr;
+  ctx->ws_bytes = bytes;
+  ctx->max_in = max_in;
+  ctx->max_out = max_out;
+  ctx->max_batch = max_batch;
+  ctx->lay = af_layout(max_in, max_out, max_batch);
+  // a fill kernel rather than a memset node, so the call is also safe under stream capture
+  hipLaunchKernelGGL(fill_int_kernel, dim3((AF_N_TICKETS + 255) / 256), dim3(256), 0, ctx->stream,
+                     (int*)(ctx->ws + ctx->lay.tickets), (int)AF_N_TICKETS, 0);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+// ---- packing -----------------------------------------------------------------------------
+// W[out][in] -> Wt[in][ld] at column col0, 32x32 tiles through LDS so both sides coalesce.
+__global__ __launch_bounds__(256) void transpose_kernel(const half_t* W, int out, int in, half_t* Wt,
+                                                        int ld, int col0) {
+  __shared__ half_t tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int i0 = blockIdx.x * 32, o0 = blockIdx.y * 32;
+  for (int r = ty; r < 32; r += 8) {
+    const int o = o0 + r, i = i0 + tx;
+    tile[r][tx] = (o < out && i < in) ? W[(size_t)o * in + i] : (half_t)0;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int i = i0 + r, o = o0 + tx;
+    if (i < in && o < out) Wt[(size_t)i * ld + col0 + o] = tile[tx][r];
+  }
+}
+
+extern "C" int af_pack_inmajor_f16(af_ctx* ctx, const void* W_f16, int out, int in, void* Wt,
+                                   int ld, int col0) {
+  if (!ctx || !W_f16 || !Wt) return AF_ENULL;
+  if (out <= 0 || in <= 0 || col0 < 0) return AF_EINVAL;
+  if (ld % 8 || col0 + out > ld) return AF_ESHAPE;
+  dim3 grid((in + 31) / 32, (out + 31) / 32);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, ctx->stream, (const half_t*)W_f16, out,
+                     in, (half_t*)Wt, ld, col0);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+// One thread quantises one group (32 input channels) of two neighbouring output columns, so
+// it owns whole bytes of the packed rows.
+__global__ __launch_bounds__(256) void pack_q4_kernel(const half_t* W, int out, int in,
+                                                      unsigned char* packed, half_t* scales, int ld,
+                                                      int col0) {
+  const int pair = blockIdx.x * blockDim.x + threadIdx.x;  // output column pair
+  const int g = blockIdx.y;                                // group along the input dim
+  if (pair * 2 >= out) return;
+  unsigned char nib[2][32];
+  for (int e = 0; e < 2; ++e) {
+    const int o = pair * 2 + e;
+    const half_t* src = W + (size_t)o * in + (size_t)g * 32;
+    float w[32];
+    float amax = 0.f;
+    for (int i = 0; i < 32; ++i) {
+      w[i] = (float)src[i];
+      amax = fmaxf(amax, fabsf(w[i]));
+    }
+    const half_t sh = (half_t)(amax / 7.0f);
+    const float s = (float)sh;
+    scales[(size_t)g * ld + col0 + o] = sh;
+    for (int i = 0; i < 32; ++i) {
+      float q = 0.f;
+      if (s != 0.f) q = fminf(7.f, fmaxf(-7.f, rintf(w[i] / s)));
+      nib[e][i] = (unsigned char)((int)q + 8);
+    }
+  }
+  for (int i = 0; i < 32; ++i)
+    packed[((size_t)g * 32 + i) * (ld / 2) + (col0 / 2) + pair] =
+        (unsigned char)(nib[0][i] | (nib[1][i] << 4));
+}
+
+extern "C" int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
+                              void* scales_f16, int ld, int col0) {
+  if (!ctx || !W_f16 || !packed || !scales_f16) return AF_ENULL;
+  if (out <= 0 || in <= 0 || col0 < 0) return AF_EINVAL;
+  if (in % 32 || out % 8 || col0 % 8 || ld % 8 || col0 + out > ld) return AF_ESHAPE;
+  dim3 grid((out / 2 + 255) / 256, in / 32);
+  hipLaunchKernelGGL(pack_q4_kernel, grid, dim3(256), 0, ctx->stream, (const half_t*)W_f16, out,
+                     in, (unsigned char*)packed, (half_t*)scales_f16, ld, col0);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+// ---- graph capture -----------------------------------------------------------------------
+extern "C" int af_capture_begin(af_ctx* ctx) {
+  if (!ctx) return AF_ENULL;
+  if (ctx->stream == nullptr) return AF_EINVAL;  // the default stream cannot be captured
+  return af_hip(hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
+}
+
+extern "C" int af_capture_end(af_ctx* ctx, af_graph** out) {
+  if (!ctx || !out) return AF_ENULL;
+  hipGraph_t g = nullptr;
+  if (hipStreamEndCapture(ctx->stream, &g) != hipSuccess || !g) return AF_EHIP;
+  hipGraphExec_t ex = nullptr;
+  if (hipGraphInstantiate(&ex, g, nullptr, nullptr, 0) != hipSuccess) {
+    (void)hipGraphDestroy(g);
+    return AF_EHIP;
+  }
+  af_graph* r = (af_graph*)calloc(1, sizeof(af_graph));
+  if (!r) return AF_EINVAL;
+  r->graph = g;
+  r->exec = ex;
+  *out = r;
+  return AF_OK;
+}
+
+extern "C" int af_graph_launch(af_ctx* ctx, af_graph* g) {
+  if (!ctx || !g) return AF_ENULL;
+  return af_hip(hipGraphLaunch(g->exec, ctx->stream));
+}
+
+extern "C" int af_graph_destroy(af_graph* g) {
+  if (!g) return AF_ENULL;
+  (void)hipGraphExecDestroy(g->exec);
+  (void)hipGraphDestroy(g->graph);
+  free(g);
+  return AF_OK;
+}

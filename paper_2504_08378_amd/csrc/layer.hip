@@ -1,0 +1,427 @@
+// Batch-1 decode step of a pre-norm decoder layer (block structure: Fig. "simplified
+// transformer layer", Section 2.2) with activation selection (operation T) in front of every
+// linear operator and the gathered GEMV (operation C) behind it; Section 3's reuse of a
+// group leader's index sets is a bit mask over the four selection points.
+//
+// Launch sequence of one layer (all on the context's stream, no host synchronisation):
+//   1 rmsnorm(hidden) [+ select]      -> x_qkv, idx0        one workgroup
+//   2 gemv  Wqkv                      -> qkv
+//   3 rope + kv append + attention    -> attn               (heads x key splits) workgroups
+//   4 select(attn)                    -> idx1
+//   5 gemv  Wo + hidden               -> h_mid
+//   6 rmsnorm(h_mid) [+ select]       -> x_gateup, idx2
+//   7 gemv  Wgateup                   -> gateup
+//   8 silu(gate)*up [+ select]        -> x_down, idx3
+//   9 gemv  Wdown + h_mid             -> hidden_out
+#include <math.h>
+
+#include "af_internal.h"
+
+#define ATT_THREADS 256
+#define ATT_WAVES (ATT_THREADS / AF_WAVE)
+#define ATT_MAX_KEYS 2048  // cache keys per (head, split) workgroup
+
+struct AttnParams {
+  const half_t* qkv;   // [q | k | v] of the new token, before rotation
+  half_t* k_cache;     // [n_kv][cap][HD]
+  half_t* v_cache;
+  half_t* out;         // [n_heads*HD]
+  float* part;         // [n_heads][KS][HD+2]
+  int* tickets;        // [n_heads]
+  int n_heads, n_kv, kv_len, kv_cap, pos;
+  float theta;
+};
+
+// Rotate the pair (a, b) = (v[i], v[i + HD/2]) by pos * theta^(-2i/HD).  The angle is formed in
+// fp64 and reduced to [-pi, pi] before the fp32 sincos, so large positions lose nothing.
+template <int HD>
+__device__ __forceinline__ void rope_pair(int i, int pos, float theta, float a, float b, float* ra,
+                                          float* rb) {
+  const double inv = exp2(-(2.0 * (double)i / (double)HD) * log2((double)theta));
+  double ang = (double)pos * inv;
+  const double two_pi = 6.283185307179586476925286766559;
+  ang -= two_pi * rint(ang / two_pi);
+  float sn, cs;
+  sincosf((float)ang, &sn, &cs);
+  *ra = a * cs - b * sn;
+  *rb = b * cs + a * sn;
+}
+
+template <int HD>
+__global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) {
+  constexpr int LPK = HD / 8;             // lanes per key (8 dims = 16 bytes each)
+  constexpr int KPW = AF_WAVE / LPK;      // keys per wave instruction
+  constexpr int KPB = ATT_THREADS / LPK;  // keys per workgroup iteration
+  __shared__ float s_q[HD];
+  __shared__ float s_knew[HD];
+  __shared__ float s_vnew[HD];
+  __shared__ float s_sc[ATT_MAX_KEYS + 1];
+  __shared__ float s_pv[KPB][HD];
+  __shared__ float s_red[ATT_WAVES];
+  __shared__ float s_m, s_l;
+  __shared__ int s_last;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.x, KS = gridDim.y, s = blockIdx.y;
+  const int rep = p.n_heads / p.n_kv, kvh = h / rep;
+  const int T = p.kv_len;
+  const int KP = (T + KS - 1) / KS;
+  const int t0 = min(s * KP, T), t1 = min(t0 + KP, T);
+  const int cnt = t1 - t0;
+  const bool owns_new = (s == KS - 1);
+  const int total = cnt + (owns_new ? 1 : 0);
+
+  const half_t* q = p.qkv + (size_t)h * HD;
+  const half_t* kn = p.qkv + (size_t)(p.n_heads + kvh) * HD;
+  const half_t* vn = p.qkv + (size_t)(p.n_heads + p.n_kv + kvh) * HD;
+  half_t* Kc = p.k_cache + (size_t)kvh * p.kv_cap * HD;
+  half_t* Vc = p.v_cache + (size_t)kvh * p.kv_cap * HD;
+
+  if (tid < HD / 2) {
+    float ra, rb;
+    rope_pair<HD>(tid, p.pos, p.theta, (float)q[tid], (float)q[tid + HD / 2], &ra, &rb);
+    const float sc = 1.0f / sqrtf((float)HD);
+    s_q[tid] = ra * sc;
+    s_q[tid + HD / 2] = rb * sc;
+  } else if (owns_new && tid >= 64 && tid < 64 + HD / 2) {
+    const int i = tid - 64;
+    float ra, rb;
+    rope_pair<HD>(i, p.pos, p.theta, (float)kn[i], (float)kn[i + HD / 2], &ra, &rb);
+    const half_t ha = (half_t)ra, hb = (half_t)rb;  // the cache holds fp16
+    s_knew[i] = (float)ha;
+    s_knew[i + HD / 2] = (float)hb;
+    if (h % rep == 0) {
+      Kc[(size_t)p.kv_len * HD + i] = ha;
+      Kc[(size_t)p.kv_len * HD + i + HD / 2] = hb;
+    }
+  } else if (owns_new && tid >= 128 && tid < 128 + HD) {
+    const int i = tid - 128;
+    const half_t v = vn[i];
+    s_vnew[i] = (float)v;
+    if (h % rep == 0) Vc[(size_t)p.kv_len * HD + i] = v;
+  }
+  __syncthreads();
+
+  // ---- scores ------------------------------------------------------------------------
+  const int lk = tid % LPK, kq = tid / LPK;  // my slice of the head dim, my key slot
+  float qr[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) qr[c] = s_q[lk * 8 + c];
+  for (int i = kq; i < cnt; i += KPB) {
+    half8 kv = *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8);
+    float d = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) d += (float)kv[c] * qr[c];
+#pragma unroll
+    for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off, AF_WAVE);
+    if (lk == 0) s_sc[i] = d;
+  }
+  if (owns_new && wave == 0) {
+    float d = 0.f;
+    for (int c = lane; c < HD; c += AF_WAVE) d += s_q[c] * s_knew[c];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, AF_WAVE);
+    if (lane == 0) s_sc[cnt] = d;
+  }
+  __syncthreads();
+
+  // ---- local softmax -----------------------------------------------------------------
+  float m = -INFINITY;
+  for (int i = tid; i < total; i += ATT_THREADS) m = fmaxf(m, s_sc[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, AF_WAVE));
+  if (lane == 0) s_red[wave] = m;
+  __syncthreads();
+  m = s_red[0];
+#pragma unroll
+  for (int w = 1; w < ATT_WAVES; ++w) m = fmaxf(m, s_red[w]);
+  __syncthreads();
+  float l = 0.f;
+  for (int i = tid; i < total; i += ATT_THREADS) {
+    float e = expf(s_sc[i] - m);
+    s_sc[i] = e;
+    l += e;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, AF_WAVE);
+  if (lane == 0) s_red[wave] = l;
+  __syncthreads();
+  l = 0.f;
+#pragma unroll
+  for (int w = 0; w < ATT_WAVES; ++w) l += s_red[w];
+
+  // ---- weighted values ---------------------------------------------------------------
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+  for (int i = kq; i < cnt; i += KPB) {
+    half8 vv = *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8);
+    const float pw = s_sc[i];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] += pw * (float)vv[c];
+  }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s_pv[kq][lk * 8 + c] = acc[c];
+  __syncthreads();
+  float* mine = p.part + ((size_t)h * KS + s) * (HD + 2);
+  if (tid < HD) {
+    float v = 0.f;
+#pragma unroll 4
+    for (int g = 0; g < KPB; ++g) v += s_pv[g][tid];
+    if (owns_new) v += s_sc[cnt] * s_vnew[tid];
+    if (KS == 1) {
+      p.out[(size_t)h * HD + tid] = (half_t)(v / l);
+    } else {
+      mine[2 + tid] = v;
+    }
+  }
+  if (KS == 1) return;
+  if (tid == 0) {
+    mine[0] = m;
+    mine[1] = l;
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    int old = __hip_atomic_fetch_add(&p.tickets[h], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == KS - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  // combine the splits in order
+  const float* base = p.part + (size_t)h * KS * (HD + 2);
+  float M = -INFINITY;
+  for (int q2 = 0; q2 < KS; ++q2)
+    M = fmaxf(M, __hip_atomic_load(base + (size_t)q2 * (HD + 2), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT));
+  if (tid < HD) {
+    float L = 0.f, v = 0.f;
+    for (int q2 = 0; q2 < KS; ++q2) {
+      const float* pp = base + (size_t)q2 * (HD + 2);
+      const float ms = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ms == -INFINITY) continue;  // an empty split
+      const float wgt = expf(ms - M);
+      L += wgt * __hip_atomic_load(pp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      v += wgt * __hip_atomic_load(pp + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    p.out[(size_t)h * HD + tid] = (half_t)(v / L);
+  }
+  if (tid == 0) p.tickets[h] = 0;
+}
+
+static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc,
+                            void* vc, int kv_len, int kv_cap, int pos, half_t* out) {
+  int KS = (kv_len + 63) / 64;
+  if (KS < 1) KS = 1;
+  if (KS > 64) KS = 64;
+  while ((size_t)cfg->n_heads * KS * (cfg->head_dim + 2) > ctx->lay.attn_floats && KS > 1) --KS;
+  if ((kv_len + KS - 1) / KS > ATT_MAX_KEYS) return AF_EINVAL;
+  AttnParams p;
+  p.qkv = qkv;
+  p.k_cache = (half_t*)kc;
+  p.v_cache = (half_t*)vc;
+  p.out = out;
+  p.part = (float*)(ctx->ws + ctx->lay.attn_part);
+  p.tickets = (int*)(ctx->ws + ctx->lay.tickets) + AF_TICKET_ATTN;
+  p.n_heads = cfg->n_heads;
+  p.n_kv = cfg->n_kv_heads;
+  p.kv_len = kv_len;
+  p.kv_cap = kv_cap;
+  p.pos = pos;
+  p.theta = cfg->rope_theta;
+  dim3 grid(cfg->n_heads, KS);
+  if (cfg->head_dim == 128)
+    hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(ATT_THREADS), 0, ctx->stream, p);
+  else
+    hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(ATT_THREADS), 0, ctx->stream, p);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+static int check_layer_args(const af_ctx* ctx, const af_layer_cfg* cfg, const af_select_cfg* sel,
+                            int kv_len, int kv_cap, int pos) {
+  if (cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->d_ffn <= 0)
+    return AF_EINVAL;
+  if (cfg->head_dim != 128 && cfg->head_dim != 64) return AF_ESHAPE;
+  if (cfg->n_heads % cfg->n_kv_heads) return AF_ESHAPE;
+  if (cfg->n_heads > AF_N_TICKETS - AF_TICKET_ATTN) return AF_ESHAPE;
+  if (cfg->d_model % 8 || cfg->d_ffn % 8) return AF_ESHAPE;
+  if (cfg->weight_kind != AF_W_F16 && cfg->weight_kind != AF_W_Q4G32) return AF_EINVAL;
+  const int qdim = cfg->n_heads * cfg->head_dim;
+  if (cfg->weight_kind == AF_W_Q4G32 && (cfg->d_model % 32 || cfg->d_ffn % 32 || qdim % 32))
+    return AF_ESHAPE;
+  if (kv_len < 0 || kv_cap <= 0 || kv_len >= kv_cap || pos < 0) return AF_EINVAL;
+  if (sel->mode != AF_SEL_TOPK && sel->mode != AF_SEL_THRESHOLD && sel->mode != AF_SEL_DENSE)
+    return AF_EINVAL;
+  const int widths[4] = {cfg->d_model, qdim, cfg->d_model, cfg->d_ffn};
+  for (int p = 0; p < 4; ++p) {
+    if (widths[p] > AF_MAX_N) return AF_ESHAPE;
+    if (sel->mode == AF_SEL_TOPK && (sel->k[p] < 0 || sel->k[p] > widths[p])) return AF_EINVAL;
+    if (sel->mode == AF_SEL_THRESHOLD && sel->t[p] != sel->t[p]) return AF_EINVAL;
+  }
+  if (!ctx->ws) return AF_EWORKSPACE;
+  const int qkv_out = (cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+  int max_w = qkv_out > 2 * cfg->d_ffn ? qkv_out : 2 * cfg->d_ffn;
+  int max_i = cfg->d_ffn > qdim ? cfg->d_ffn : qdim;
+  if (cfg->d_model > max_i) max_i = cfg->d_model;
+  if (max_w > ctx->max_out || max_i > ctx->max_in) return AF_EWORKSPACE;
+  return AF_OK;
+}
+
+// One layer.  `own` receives the sets of points that select here; `src` provides the sets of
+// points whose bit is set in reuse (own == src unless the layer follows a group leader).
+static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
+                     const half_t* h_in, half_t* h_out, void* kc, void* vc, int kv_len,
+                     int kv_cap, int pos, const af_select_cfg* sel, unsigned reuse,
+                     const af_idx_sets* own, const af_idx_sets* src) {
+  const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim;
+  const int qdim = cfg->n_heads * hd, qkv_out = (cfg->n_heads + 2 * cfg->n_kv_heads) * hd;
+  half_t* act[7];
+  for (int i = 0; i < 7; ++i) act[i] = (half_t*)(ctx->ws + ctx->lay.act[i]);
+  half_t *x0 = act[0], *qkv = act[1], *attn = act[2], *hmid = act[3], *x2 = act[4], *gu = act[5],
+         *x3 = act[6];
+  const bool q4 = cfg->weight_kind == AF_W_Q4G32;
+  int rc;
+
+  struct Point {
+    const int32_t* idx;
+    int nidx_host;
+    const int32_t* nidx_dev;
+  } pt[4];
+  const int widths[4] = {d, qdim, d, f};
+  for (int p = 0; p < 4; ++p) {
+    const bool reused = (reuse >> p) & 1u;
+    const af_idx_sets* ss = reused ? src : own;
+    if (sel->mode == AF_SEL_DENSE && !reused) {
+      pt[p] = {nullptr, widths[p], nullptr};
+    } else if (sel->mode == AF_SEL_TOPK) {
+      pt[p] = {ss->idx[p], sel->k[p], nullptr};
+    } else {  // threshold, or a reused set under dense/threshold: the count lives on the device
+      pt[p] = {ss->idx[p], widths[p], ss->count[p]};
+    }
+  }
+
+  auto select_at = [&](int p, int producer, const half_t* src_v, const half_t* gain,
+                       half_t* x_out) -> int {
+    af_select_args a{};
+    a.src = src_v;
+    a.gain = gain;
+    a.x_out = x_out;
+    a.n = widths[p];
+    a.eps = cfg->rms_eps;
+    const bool reused = (reuse >> p) & 1u;
+    a.mode = reused ? AF_SEL_DENSE : sel->mode;  // a reused point only runs the producer
+    a.k = sel->k[p];
+    a.t = sel->t[p];
+    a.idx = own->idx[p];
+    a.count = own->count[p];
+    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;  // nothing to do
+    if (a.mode == AF_SEL_TOPK && a.k == 0) a.mode = AF_SEL_DENSE;         // empty set
+    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;
+    return af_launch_select(ctx, producer, a);
+  };
+  auto gemv = [&](int p, const void* W, const void* Sc, int in, int out, const half_t* x,
+                  half_t* y, const half_t* res) -> int {
+    af_gemv_args a{};
+    a.W = W;
+    a.scales = (const half_t*)Sc;
+    a.in = in;
+    a.out = out;
+    a.ld = out;
+    a.x = x;
+    a.idx = pt[p].idx;
+    a.nidx_host = pt[p].nidx_host;
+    a.nidx_dev = pt[p].nidx_dev;
+    a.y = y;
+    a.y_kind = AF_F16;
+    a.residual = res;
+    return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a);
+  };
+
+  if ((rc = select_at(0, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0))) return rc;
+  if ((rc = gemv(0, w->Wqkv, w->Sqkv, d, qkv_out, x0, qkv, nullptr))) return rc;
+  if ((rc = launch_attention(ctx, cfg, qkv, kc, vc, kv_len, kv_cap, pos, attn))) return rc;
+  if ((rc = select_at(1, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
+  if ((rc = gemv(1, w->Wo, w->So, qdim, d, attn, hmid, h_in))) return rc;
+  if ((rc = select_at(2, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2))) return rc;
+  if ((rc = gemv(2, w->Wgateup, w->Sgateup, d, 2 * f, x2, gu, nullptr))) return rc;
+  if ((rc = select_at(3, AF_PRO_SILUMUL, gu, nullptr, x3))) return rc;
+  if ((rc = gemv(3, w->Wdown, w->Sdown, f, d, x3, h_out, hmid))) return rc;
+  return AF_OK;
+}
+
+static int check_layer_ptrs(const af_layer_cfg* cfg, const af_layer_weights* w,
+                            const af_select_cfg* sel, unsigned reuse, const af_idx_sets* own,
+                            const af_idx_sets* src) {
+  if (!w->Wqkv || !w->Wo || !w->Wgateup || !w->Wdown || !w->g_attn_norm || !w->g_ffn_norm)
+    return AF_ENULL;
+  if (cfg->weight_kind == AF_W_Q4G32 && (!w->Sqkv || !w->So || !w->Sgateup || !w->Sdown))
+    return AF_ENULL;
+  for (int p = 0; p < 4; ++p) {
+    const bool reused = (reuse >> p) & 1u;
+    if (!reused && sel->mode == AF_SEL_DENSE) continue;
+    const af_idx_sets* ss = reused ? src : own;
+    if (!ss || !ss->idx[p]) return AF_ENULL;
+    if (sel->mode != AF_SEL_TOPK && !ss->count[p]) return AF_ENULL;
+  }
+  return AF_OK;
+}
+
+extern "C" int af_decode_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
+                               const void* hidden_in, void* hidden_out, void* k_cache,
+                               void* v_cache, int kv_len, int kv_cap, int pos,
+                               const af_select_cfg* sel, af_idx_sets* sets) {
+  if (!ctx || !cfg || !w || !hidden_in || !hidden_out || !k_cache || !v_cache || !sel)
+    return AF_ENULL;
+  int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
+  if (rc) return rc;
+  if ((rc = check_layer_ptrs(cfg, w, sel, sel->reuse_mask & 15u, sets, sets))) return rc;
+  return run_layer(ctx, cfg, w, (const half_t*)hidden_in, (half_t*)hidden_out, k_cache, v_cache,
+                   kv_len, kv_cap, pos, sel, sel->reuse_mask & 15u, sets, sets);
+}
+
+extern "C" int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
+                               int n_layers, const void* hidden_in, void* hidden_out,
+                               void* const* k_caches, void* const* v_caches, int kv_len,
+                               int kv_cap, int pos, const af_select_cfg* sel, int group,
+                               unsigned reuse_points, af_idx_sets* sets) {
+  if (!ctx || !cfg || !w || !hidden_in || !hidden_out || !k_caches || !v_caches || !sel)
+    return AF_ENULL;
+  if (n_layers <= 0 || group < 1) return AF_EINVAL;
+  int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
+  if (rc) return rc;
+  // validate every layer before the first launch
+  for (int l = 0; l < n_layers; ++l) {
+    if (!k_caches[l] || !v_caches[l]) return AF_ENULL;
+    const bool follower = group > 1 && (l % group) != 0;
+    const unsigned reuse = (sel->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
+    const af_idx_sets* own = sets ? &sets[l] : nullptr;
+    const af_idx_sets* src = sets ? &sets[follower ? l - l % group : l] : nullptr;
+    if (!own && sel->mode != AF_SEL_DENSE) return AF_ENULL;
+    if (!own && reuse) return AF_ENULL;
+    static const af_idx_sets none = {};
+    if ((rc = check_layer_ptrs(cfg, &w[l], sel, reuse, own ? own : &none, src ? src : &none)))
+      return rc;
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    const bool follower = group > 1 && (l % group) != 0;
+    const unsigned reuse = (sel->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
+    static const af_idx_sets none = {};
+    const af_idx_sets* own = sets ? &sets[l] : &none;
+    const af_idx_sets* src = sets ? &sets[follower ? l - l % group : l] : &none;
+    const half_t* hin = (const half_t*)(l == 0 ? hidden_in : hidden_out);
+    rc = run_layer(ctx, cfg, &w[l], hin, (half_t*)hidden_out, k_caches[l], v_caches[l], kv_len,
+                   kv_cap, pos, sel, reuse, own, src);
+    if (rc) return rc;
+  }
+  return AF_OK;
+}
+
+extern "C" int af_layer_tap(af_ctx* ctx, int which, const void** dev_ptr) {
+  if (!ctx || !dev_ptr) return AF_ENULL;
+  if (which < 0 || which > 6) return AF_EINVAL;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  *dev_ptr = ctx->ws + ctx->lay.act[which];
+  return AF_OK;
+}

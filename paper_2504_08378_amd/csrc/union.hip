@@ -1,0 +1,287 @@
+// Small-batch decode over the union of the tokens' active sets (extension of Section 4's
+// operation C from one token to B <= 8 tokens; the paper itself decodes one token at a time).
+//
+//   Y[b][o] = sum_{j in idx_b[b]} Wt[j][o] * X[b][j]
+//
+// Step 1 (one workgroup): scatter the B index lists into a per-channel bit mask in LDS, emit
+// the ascending union U, and write Xm[j][b] = X[b][j] if token b keeps channel j else 0
+// (fp16, 8 tokens per row = one 16-byte load in the GEMV).
+// Step 2: the gathered GEMV of gemv_f16.hip over U with B accumulator sets per lane; every
+// weight row of the union is read once for all tokens.
+#include "af_internal.h"
+
+#define UB_THREADS 1024
+#define UB_WAVES (UB_THREADS / AF_WAVE)
+
+struct UnionBuildParams {
+  const half_t* X;         // [B][in]
+  const int32_t* idx_b;    // [B][k]
+  int32_t* union_idx;      // [in]
+  int32_t* union_n;        // [1]
+  half_t* Xm;              // [in][8]
+  int B, k, in;
+};
+
+__global__ __launch_bounds__(UB_THREADS) void union_build_kernel(UnionBuildParams p) {
+  extern __shared__ unsigned s_mask[];  // one word per channel (bit b = token b keeps it)
+  __shared__ unsigned s_wtot[UB_WAVES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int j = tid; j < p.in; j += UB_THREADS) s_mask[j] = 0;
+  __syncthreads();
+  for (int b = 0; b < p.B; ++b)
+    for (int t = tid; t < p.k; t += UB_THREADS) atomicOr(&s_mask[p.idx_b[(size_t)b * p.k + t]], 1u << b);
+  __syncthreads();
+  // masked, transposed token values
+  for (int j = tid; j < p.in; j += UB_THREADS) {
+    const unsigned m = s_mask[j];
+    half8 v;
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+      v[b] = (b < p.B && ((m >> b) & 1u)) ? p.X[(size_t)b * p.in + j] : (half_t)0;
+    *reinterpret_cast<half8*>(p.Xm + (size_t)j * 8) = v;
+  }
+  // ordered compaction: each thread owns a contiguous chunk of channels
+  const int c = (p.in + UB_THREADS - 1) / UB_THREADS;
+  const int j0 = min(tid * c, p.in), j1 = min(j0 + c, p.in);
+  unsigned cnt = 0;
+  for (int j = j0; j < j1; ++j) cnt += s_mask[j] != 0;
+  unsigned inc = cnt;
+#pragma unroll
+  for (int off = 1; off < AF_WAVE; off <<= 1) {
+    unsigned o = __shfl_up(inc, off, AF_WAVE);
+    if (lane >= off) inc += o;
+  }
+  if (lane == 63) s_wtot[wave] = inc;
+  __syncthreads();
+  unsigned base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < UB_WAVES; ++w) {
+    unsigned t = s_wtot[w];
+    if (w < wave) base += t;
+    total += t;
+  }
+  unsigned pos = base + inc - cnt;
+  for (int j = j0; j < j1; ++j)
+    if (s_mask[j] != 0) p.union_idx[pos++] = j;
+  if (tid == 0) *p.union_n = (int)total;
+}
+
+#define UG_THREADS 256
+#define UG_WAVES (UG_THREADS / AF_WAVE)
+#define UG_CHUNK 512
+
+struct UnionGemvParams {
+  const half_t* W;
+  const half_t* Xm;        // [in][8]
+  const int32_t* idx;      // union
+  const int32_t* nidx_dev;
+  float* partials;         // [S][B][out_pad]
+  int* tickets;
+  void* Y;                 // [B][out]
+  int out, ld, nidx_host, y_kind, out_pad, B;
+};
+
+template <int NB, int LX, int U>
+__global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams p) {
+  constexpr int LY = AF_WAVE / LX;
+  constexpr int TW = LX * 8;
+  constexpr int STEP = UG_WAVES * LY;
+  __shared__ int s_idx[UG_CHUNK];
+  __shared__ half8 s_xm[UG_CHUNK];
+  __shared__ float s_red[UG_WAVES][NB][TW];
+  __shared__ int s_last;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lx = lane % LX, ly = lane / LX;
+  const int col = blockIdx.x * TW + lx * 8;
+  const int col_ld = col < p.out ? col : 0;
+  const int S = gridDim.y, s = blockIdx.y;
+
+  const int nidx = min(*p.nidx_dev, p.nidx_host);
+  const int R = (nidx + S - 1) / S;
+  const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+
+  float acc[NB][8];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
+  const half_t* wcol = p.W + col_ld;
+
+  for (int base = r0; base < r1; base += UG_CHUNK) {
+    const int cnt = min(UG_CHUNK, r1 - base);
+    __syncthreads();
+    for (int i = tid; i < cnt; i += UG_THREADS) {
+      const int j = p.idx[base + i];
+      s_idx[i] = j;
+      s_xm[i] = *reinterpret_cast<const half8*>(p.Xm + (size_t)j * 8);
+    }
+    __syncthreads();
+    int i = wave * LY + ly;
+    for (; i + (U - 1) * STEP < cnt; i += U * STEP) {
+      half8 w[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const half8 xm = s_xm[i + u * STEP];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const float xv = (float)xm[b];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[b][c] += (float)w[u][c] * xv;
+        }
+      }
+    }
+    for (; i < cnt; i += STEP) {
+      const half8 w = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i] * p.ld);
+      const half8 xm = s_xm[i];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const float xv = (float)xm[b];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[b][c] += (float)w[c] * xv;
+      }
+    }
+  }
+
+#pragma unroll
+  for (int off = LX; off < AF_WAVE; off <<= 1)
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], off, AF_WAVE);
+  if (ly == 0) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) s_red[wave][b][lx * 8 + c] = acc[b][c];
+  }
+  __syncthreads();
+
+  const int tile0 = blockIdx.x * TW;
+  auto store = [&](int b, int colg, float v) {
+    if (b < p.B && colg < p.out) {
+      if (p.y_kind == AF_F16)
+        reinterpret_cast<half_t*>(p.Y)[(size_t)b * p.out + colg] = (half_t)v;
+      else
+        reinterpret_cast<float*>(p.Y)[(size_t)b * p.out + colg] = v;
+    }
+  };
+  if (S == 1) {
+    for (int e = tid; e < NB * TW; e += UG_THREADS) {
+      const int b = e / TW, c = e % TW;
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < UG_WAVES; ++w) v += s_red[w][b][c];
+      store(b, tile0 + c, v);
+    }
+    return;
+  }
+  float* mine = p.partials + (size_t)s * NB * p.out_pad;
+  for (int e = tid; e < NB * TW; e += UG_THREADS) {
+    const int b = e / TW, c = e % TW;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < UG_WAVES; ++w) v += s_red[w][b][c];
+    mine[(size_t)b * p.out_pad + tile0 + c] = v;
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    int old = __hip_atomic_fetch_add(&p.tickets[blockIdx.x], 1, __ATOMIC_ACQ_REL,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == S - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int e = tid; e < NB * TW; e += UG_THREADS) {
+    const int b = e / TW, c = e % TW;
+    float v = 0.f;
+    for (int q = 0; q < S; ++q)
+      v += __hip_atomic_load(p.partials + ((size_t)q * NB + b) * p.out_pad + tile0 + c,
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    store(b, tile0 + c, v);
+  }
+  if (tid == 0) p.tickets[blockIdx.x] = 0;
+}
+
+extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                        const void* X_f16, int B, const int32_t* idx_b, int k,
+                                        int32_t* union_idx, int32_t* union_n, void* Y, int y_kind) {
+  if (!ctx || !Wt || !X_f16 || !union_idx || !union_n || !Y || (!idx_b && k > 0)) return AF_ENULL;
+  if (in <= 0 || out <= 0 || in > AF_MAX_N || B < 1 || B > AF_MAX_BATCH || k < 0 || k > in)
+    return AF_EINVAL;
+  if (out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
+  if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  if (in > ctx->max_in || out > ctx->max_out || B > ctx->max_batch) return AF_EWORKSPACE;
+
+  UnionBuildParams bp;
+  bp.X = (const half_t*)X_f16;
+  bp.idx_b = idx_b;
+  bp.union_idx = union_idx;
+  bp.union_n = union_n;
+  bp.Xm = (half_t*)(ctx->ws + ctx->lay.union_x);
+  bp.B = B;
+  bp.k = k;
+  bp.in = in;
+  static bool lds_attr_set = false;
+  if (!lds_attr_set) {  // up to 128 KB of dynamic LDS for the channel masks
+    lds_attr_set = true;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(union_build_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(AF_MAX_N * sizeof(unsigned)));
+  }
+  hipLaunchKernelGGL(union_build_kernel, dim3(1), dim3(UB_THREADS), (size_t)in * sizeof(unsigned),
+                     ctx->stream, bp);
+  AF_LAUNCH_CHECK();
+
+  const int NB = B == 1 ? 1 : (B == 2 ? 2 : (B <= 4 ? 4 : 8));
+  const int lx = (out <= 2048) ? 16 : 32;
+  const int tw = lx * 8;
+  const int tiles = (out + tw - 1) / tw;
+  const int out_pad = tiles * tw;
+  if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
+  const int nidx_max = (long long)B * k < in ? B * k : in;
+  int S = (ctx->n_cu * 8 + tiles - 1) / tiles;
+  int max_s = (nidx_max + 31) / 32;
+  if (max_s < 1) max_s = 1;
+  if (S > max_s) S = max_s;
+  if (S > 256) S = 256;
+  while (S > 1 && (size_t)S * NB * out_pad > ctx->lay.partial_floats) --S;
+
+  UnionGemvParams p;
+  p.W = (const half_t*)Wt;
+  p.Xm = bp.Xm;
+  p.idx = union_idx;
+  p.nidx_dev = union_n;
+  p.partials = (float*)(ctx->ws + ctx->lay.partials);
+  p.tickets = (int*)(ctx->ws + ctx->lay.tickets);
+  p.Y = Y;
+  p.out = out;
+  p.ld = ld;
+  p.nidx_host = nidx_max;
+  p.y_kind = y_kind;
+  p.out_pad = out_pad;
+  p.B = B;
+  dim3 grid(tiles, S), block(UG_THREADS);
+#define UNION_LAUNCH(NBV, LXV, UV) \
+  hipLaunchKernelGGL((gemv_union_kernel<NBV, LXV, UV>), grid, block, 0, ctx->stream, p)
+  if (lx == 16) {
+    if (NB == 1) UNION_LAUNCH(1, 16, 8);
+    else if (NB == 2) UNION_LAUNCH(2, 16, 8);
+    else if (NB == 4) UNION_LAUNCH(4, 16, 4);
+    else UNION_LAUNCH(8, 16, 4);
+  } else {
+    if (NB == 1) UNION_LAUNCH(1, 32, 8);
+    else if (NB == 2) UNION_LAUNCH(2, 32, 8);
+    else if (NB == 4) UNION_LAUNCH(4, 32, 4);
+    else UNION_LAUNCH(8, 32, 4);
+  }
+#undef UNION_LAUNCH
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}

@@ -1,0 +1,140 @@
+"""Device-resident decoder stack: uploads host weights, packs them through the C ABI into the
+fused in-major layout, owns the KV caches / index-set buffers, and marshals the layer and
+stack calls.  Buffers and pointers only; every computation happens in libactiveflow.so."""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def layer_cfg(shape, weight_kind=B.AF_W_F16, rms_eps=1e-5, rope_theta=10000.0) -> B.LayerCfg:
+    return B.LayerCfg(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                      rms_eps, rope_theta, weight_kind)
+
+
+def select_cfg(mode, k=(0, 0, 0, 0), t=(0.0, 0.0, 0.0, 0.0), reuse_mask=0) -> B.SelectCfg:
+    s = B.SelectCfg()
+    s.mode = mode
+    for p in range(4):
+        s.k[p] = int(k[p])
+        s.t[p] = float(t[p])
+    s.reuse_mask = reuse_mask
+    return s
+
+
+class DeviceLayer:
+    """Packed weights of one layer.  `host` maps Wq, Wk, Wv, Wo, Wgate, Wup, Wdown (fp16
+    [out][in] NumPy arrays) and g_attn, g_ffn."""
+
+    def __init__(self, ctx: B.Context, shape, host: dict, weight_kind=B.AF_W_F16):
+        self.ctx, self.shape, self.kind = ctx, shape, weight_kind
+        d, f, hd = shape.d_model, shape.d_ffn, shape.head_dim
+        nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
+        dev = ctx.device
+        self.keep = []
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+        def fused(parts, n_in):
+            ld = sum(p.shape[0] for p in parts)
+            if weight_kind == B.AF_W_F16:
+                Wt = torch.empty((n_in, ld), dtype=torch.float16, device=dev)
+                S = None
+            else:
+                Wt = torch.empty((n_in, ld // 2), dtype=torch.uint8, device=dev)
+                S = torch.empty((n_in // 32, ld), dtype=torch.float16, device=dev)
+            col = 0
+            for p in parts:
+                Wd = up(p)
+                torch.cuda.current_stream().synchronize()
+                if weight_kind == B.AF_W_F16:
+                    ctx.pack_inmajor_f16(Wd, Wt, col0=col)
+                else:
+                    ctx.pack_q4_g32(Wd, Wt, S, col0=col)
+                ctx.synchronize()
+                col += p.shape[0]
+                del Wd
+            return Wt, S
+
+        self.Wqkv, self.Sqkv = fused([host["Wq"], host["Wk"], host["Wv"]], d)
+        self.Wo, self.So = fused([host["Wo"]], nq)
+        self.Wgateup, self.Sgateup = fused([host["Wgate"], host["Wup"]], d)
+        self.Wdown, self.Sdown = fused([host["Wdown"]], f)
+        self.g_attn = up(host["g_attn"])
+        self.g_ffn = up(host["g_ffn"])
+        torch.cuda.current_stream().synchronize()
+
+    def struct(self) -> B.LayerWeights:
+        p = lambda t: t.data_ptr() if t is not None else None
+        return B.LayerWeights(p(self.Wqkv), p(self.Wo), p(self.Wgateup), p(self.Wdown),
+                              p(self.Sqkv), p(self.So), p(self.Sgateup), p(self.Sdown),
+                              p(self.g_attn), p(self.g_ffn))
+
+
+class IdxSetBuffers:
+    """Device buffers for the four index sets of one layer."""
+
+    def __init__(self, ctx: B.Context, shape):
+        widths = (shape.d_model, shape.n_heads * shape.head_dim, shape.d_model, shape.d_ffn)
+        self.widths = widths
+        self.idx = [torch.zeros(w, dtype=torch.int32, device=ctx.device) for w in widths]
+        self.count = [torch.zeros(1, dtype=torch.int32, device=ctx.device) for _ in widths]
+
+    def struct(self) -> B.IdxSets:
+        s = B.IdxSets()
+        for p in range(4):
+            s.idx[p] = self.idx[p].data_ptr()
+            s.count[p] = self.count[p].data_ptr()
+        return s
+
+    def load(self, sets):
+        """Copy host index lists in (for forced / reused sets)."""
+        for p in range(4):
+            if sets[p] is None:
+                continue
+            a = np.asarray(sets[p], dtype=np.int32)
+            self.idx[p][: a.size] = torch.from_numpy(a).to(self.idx[p].device)
+            self.count[p].fill_(int(a.size))
+        torch.cuda.current_stream().synchronize()
+
+    def fetch(self, p: int, n: int | None = None) -> np.ndarray:
+        if n is None:
+            n = int(self.count[p].item())
+        return self.idx[p][:n].cpu().numpy()
+
+
+class DeviceStack:
+    """A stack of DeviceLayers with KV caches and per-layer index-set buffers."""
+
+    def __init__(self, ctx: B.Context, shape, layers: list, kv: list, kv_cap: int,
+                 weight_kind=B.AF_W_F16):
+        self.ctx, self.shape, self.kind = ctx, shape, weight_kind
+        self.layers = layers
+        self.n_layers = len(layers)
+        dev = ctx.device
+        self.K = [torch.from_numpy(k).to(dev) for k, _ in kv]
+        self.V = [torch.from_numpy(v).to(dev) for _, v in kv]
+        self.kv_cap = kv_cap
+        self.sets = [IdxSetBuffers(ctx, shape) for _ in layers]
+        self.cfg = layer_cfg(shape, weight_kind)
+        self.w_array = (B.LayerWeights * self.n_layers)(*[l.struct() for l in layers])
+        self.sets_array = (B.IdxSets * self.n_layers)(*[s.struct() for s in self.sets])
+        self.k_ptrs = (C.c_void_p * self.n_layers)(*[k.data_ptr() for k in self.K])
+        self.v_ptrs = (C.c_void_p * self.n_layers)(*[v.data_ptr() for v in self.V])
+        self.hidden_out = torch.zeros(shape.d_model, dtype=torch.float16, device=dev)
+        torch.cuda.current_stream().synchronize()
+
+    def layer(self, l: int, hidden_in, hidden_out, kv_len: int, pos: int, sel: B.SelectCfg):
+        self.ctx.decode_layer(self.cfg, self.layers[l].struct(), hidden_in, hidden_out, self.K[l],
+                              self.V[l], kv_len, self.kv_cap, pos, sel, self.sets[l].struct())
+
+    def run(self, hidden_in, kv_len: int, pos: int, sel: B.SelectCfg, group: int = 1,
+            reuse_points: int = 0, hidden_out=None):
+        out = self.hidden_out if hidden_out is None else hidden_out
+        self.ctx.decode_stack(self.cfg, self.w_array, self.n_layers, hidden_in, out, self.k_ptrs,
+                              self.v_ptrs, kv_len, self.kv_cap, pos, sel, group, reuse_points,
+                              self.sets_array)
+        return out
