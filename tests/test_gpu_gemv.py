@@ -47,7 +47,7 @@ def test_config0(ctx):
     idx = O.select_topk(x, 1024)
     for kind in (B.AF_F16, B.AF_F32):
         y = _run(ctx, W, x, idx, y_kind=kind)
-        assert O.rel_err(y, O.sparse_gemv(W, x, idx)) <= (TOL if kind == B.AF_F16 else 2e-5)
+        assert O.rel_err(y, O.sparse_gemv(W, x, idx)) <= (TOL if kind == B.AF_F16 else 1e-4)
 
 
 @pytest.mark.parametrize("out,n,k", [(8, 1, 1), (8, 33, 17), (136, 100, 50), (520, 777, 300),
@@ -160,7 +160,7 @@ def test_union_small_batch(ctx, Bt, out, n):
     ref = O.union_gemv(W, X, list(idx_b))
     Yh = to_host(Y)
     for b in range(Bt):
-        assert O.rel_err(Yh[b], ref[b]) <= 2e-5
+        assert O.rel_err(Yh[b], ref[b]) <= 1e-4
     Y16, _, _ = ctx.sparse_gemv_union_f16(Wt, to_dev(X), to_dev(idx_b))
     ctx.synchronize()
     for b in range(Bt):
@@ -179,4 +179,4 @@ def test_union_identical_tokens_and_b1_equals_single(ctx):
     assert int(to_host(un)[0]) == 192 and np.array_equal(to_host(U)[:192], idx)
     Yh = to_host(Y)
     assert all(np.array_equal(Yh[0], Yh[b]) for b in range(4))
-    assert O.rel_err(Yh[0], O.sparse_gemv(W, x, idx)) <= 2e-5
+    assert O.rel_err(Yh[0], O.sparse_gemv(W, x, idx)) <= 1e-4

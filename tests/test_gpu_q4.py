@@ -39,7 +39,7 @@ def test_q4_gemv(ctx, out, n, k):
     nib, s = O.quantize_q4_g32(W)
     idx = O.select_topk(x, k)
     packed, scales = ctx.pack_q4_g32(to_dev(W))
-    for kind, tol in ((B.AF_F32, 5e-5), (B.AF_F16, TOL)):
+    for kind, tol in ((B.AF_F32, 1e-4), (B.AF_F16, TOL)):
         y = ctx.sparse_gemv_q4(packed, scales, to_dev(x), to_dev(idx), y_kind=kind)
         ctx.synchronize()
         assert O.rel_err(to_host(y), O.sparse_gemv_q4(nib, s, x, idx)) <= tol, kind
