@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the active-weight decode hot path on one MI355X.
+
+A step is one batch-1 decode of one token through the whole 7B-shape stack (32 layers,
+d_model 4096, FFN 11008, 32 heads, 512-token KV cache) at 50 % activation sparsity: four
+selections and four gathered GEMVs per layer plus norm, rotary attention and SwiGLU glue,
+replayed as one HIP graph.  Weights, caches and the input state are synthetic (seeded) and
+already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: decode tokens/s (value), the active-weight GB/s it corresponds to,
+the HBM roofline of the dominant kernel (the gate|up gathered GEMV) measured live with
+events on the library's stream, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs (FETCH_SIZE and
+# WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
+TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def keep_count(n: int, sp: int) -> int:
+    return n - (sp * n) // 100
+
+
+def gemv_bytes(k: int, out: int, residual: bool = False) -> int:
+    """Algorithmic bytes of one gathered GEMV: k active rows of out fp16 weights, their
+    (x, idx) pairs, and the fp16 result (plus the residual it adds)."""
+    return k * (out * 2 + 6) + out * 2 + (out * 2 if residual else 0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--shape", default="7b")
+    ap.add_argument("--layers", type=int, default=0, help="0 = all layers of the shape")
+    ap.add_argument("--sparsity", type=int, default=50)
+    ap.add_argument("--weights", default="f16", choices=["f16", "q4"])
+    ap.add_argument("--group", type=int, default=1, help="cross-layer reuse group (1 = none)")
+    ap.add_argument("--reuse-points", type=lambda s: int(s, 0), default=0b1111)
+    ap.add_argument("--kv-len", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as S
+    from paper_2504_08378_amd import binding as B
+    from paper_2504_08378_amd import model as M
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+
+    base = S.MODEL_SHAPES[args.shape]
+    L = args.layers or base.n_layers
+    shape = base
+    sp = args.sparsity
+    kind = B.AF_W_F16 if args.weights == "f16" else B.AF_W_Q4G32
+    kv_len, kv_cap = args.kv_len, args.kv_len + 16
+    widths = (shape.d_model, shape.n_heads * shape.head_dim, shape.d_model, shape.d_ffn)
+    ks = tuple(keep_count(n, sp) for n in widths)
+
+    ctx = B.Context(0)
+    t_build = time.time()
+    layers, kv, host_layer0 = [], [], None
+    for l in range(L):
+        w = S.device_layer_weights(0, shape, l)
+        if l == 0 and not args.no_cpu_baseline:
+            host_layer0 = {k: v.cpu().numpy() for k, v in w.items()}
+        layers.append(M.DeviceLayer(ctx, shape, w, kind))
+        kv.append(S.device_kv_cache(0, shape, l, kv_cap, kv_len))
+        del w
+    st = M.DeviceStack(ctx, shape, layers, kv, kv_cap, kind)
+    h_host = S.activation(0, S.channel_scales(0, shape.d_model, shape.name), "hidden", 0)
+    hin = torch.from_numpy(h_host).cuda()
+    torch.cuda.synchronize()
+    t_build = time.time() - t_build
+
+    sel = M.select_cfg(B.AF_SEL_TOPK, ks)
+    run = lambda: st.run(hin, kv_len, kv_len, sel, group=args.group, reuse_points=args.reuse_points)
+    run()
+    ctx.synchronize()
+    graph = None
+    if not args.no_graph:
+        ctx.capture_begin()
+        run()
+        graph = ctx.capture_end()
+        step = lambda: ctx.graph_launch(graph)
+    else:
+        step = run
+
+    for _ in range(args.warmup):
+        step()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tok_s = args.steps / dt
+
+    # active weight bytes of one token (the four operators of every layer)
+    bpw = 2.0 if kind == B.AF_W_F16 else 0.5
+    per_layer = (ks[0] * shape.qkv_out + ks[1] * shape.d_model + ks[2] * 2 * shape.d_ffn
+                 + ks[3] * shape.d_model) * bpw
+    if kind == B.AF_W_Q4G32:   # every scale row is touched at these sparsities
+        per_layer += (shape.d_model // 32 * shape.qkv_out + widths[1] // 32 * shape.d_model
+                      + shape.d_model // 32 * 2 * shape.d_ffn + shape.d_ffn // 32 * shape.d_model) * 2
+    active_bytes = per_layer * L
+
+    # ---- roofline of the dominant kernel: the gate|up gathered GEMV, timed alone --------
+    # One launch per layer, rotating through all layers' matrices (far more than the
+    # 256 MB last-level cache), bracketed by events on the library's stream.
+    x2 = torch.from_numpy(S.activation(0, S.channel_scales(0, shape.d_model, "roof"), "roof", 0)).cuda()
+    idx2 = st.sets[0].idx[2]          # ascending top-k set of layer 0's gate/up input
+    y2 = torch.empty(2 * shape.d_ffn, dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+
+    def gateup(l):
+        lay = st.layers[l]
+        if kind == B.AF_W_F16:
+            ctx.sparse_gemv_f16(lay.Wgateup, x2, idx2, nidx=ks[2], y=y2)
+        else:
+            ctx.sparse_gemv_q4(lay.Wgateup, lay.Sgateup, x2, idx2, nidx=ks[2], y=y2)
+
+    reps = max(1, 256 // L)
+    for l in range(L):
+        gateup(l)
+    ctx.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(ctx.stream)
+    for _ in range(reps):
+        for l in range(L):
+            gateup(l)
+    e1.record(ctx.stream)
+    ctx.synchronize()
+    launches = reps * L
+    us_per_launch = e0.elapsed_time(e1) * 1e3 / launches
+    if kind == B.AF_W_F16:
+        alg = gemv_bytes(ks[2], 2 * shape.d_ffn)
+    else:
+        alg = ks[2] * (shape.d_ffn + 6) + (shape.d_model // 32) * 2 * shape.d_ffn * 2 + 2 * shape.d_ffn * 2
+    achieved = alg / (us_per_launch * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemv_f16_kernel (gate|up)" if kind == B.AF_W_F16 else "gemv_q4_kernel (gate|up)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "bytes_per_launch": alg, "us_per_launch": round(us_per_launch, 3), "launches": launches}
+
+    # ---- CPU oracle on a bounded sample ------------------------------------------------
+    cpu = None
+    if host_layer0 is not None:
+        from oracle import activeflow_oracle as O          # cpu_baseline leg only
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        ocfg = O.LayerCfg(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn)
+        K0, V0 = [t.cpu().numpy() for t in kv[0]]
+        wq = host_layer0
+        if kind == B.AF_W_Q4G32:
+            wq = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in host_layer0.items()}
+        n_done, t_cpu, h = 0, 0.0, h_host
+        tr = None
+        while n_done < 4 and t_cpu < 10.0:
+            t1 = time.perf_counter()
+            tr = O.decode_layer(ocfg, wq, h, K0.copy(), V0.copy(), kv_len, kv_len,
+                                O.SelectCfg(O.SEL_TOPK, ks), weights_q4=(kind == B.AF_W_Q4G32))
+            t_cpu += time.perf_counter() - t1
+            n_done += 1
+            if n_done == 1:
+                first = tr
+        cpu_tok_s = 1.0 / (t_cpu / n_done * L)
+        cpu = {"value": round(cpu_tok_s, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"layer 0 of the stack decoded {n_done}x by the fp64 NumPy oracle "
+                         f"({t_cpu:.1f} s), scaled to {L} layers"}
+        # correctness of the timed buffers: layer 0 of the GPU stack against the oracle
+        st.layer(0, hin, st.hidden_out, kv_len, kv_len, sel)
+        ctx.synchronize()
+        got0 = st.sets[0].fetch(0, ks[0])
+        if not np.array_equal(got0, first.idx[0]):
+            print("bench.py: WARNING layer-0 qkv index set differs from the oracle", file=sys.stderr)
+        st.sets[0].load(first.idx)
+        st.layer(0, hin, st.hidden_out, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+        ctx.synchronize()
+        err = O.rel_err(st.hidden_out.cpu().numpy(), first.hidden)
+        cpu["gpu_vs_oracle_rel_err_layer0"] = float(f"{err:.3e}")
+        if err > 2e-3:
+            print(f"bench.py: WARNING layer-0 output differs from the oracle: {err}", file=sys.stderr)
+
+    wl = f"{args.shape}-shape decoder stack, {L} layers, batch-1 decode, {args.weights} weights, " \
+         f"{sp}% sparsity at qkv/o/gate-up/down, {kv_len}-token KV cache"
+    if args.group > 1:
+        wl += f", index reuse in groups of {args.group} (points mask {args.reuse_points:#06b})"
+    out = {
+        "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+        "value": round(tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16" if kind == B.AF_W_F16 else "int4",
+        "data": "synthetic",
+        "config": {"workload": wl, "layers": L, "d_model": shape.d_model, "d_ffn": shape.d_ffn,
+                   "k": list(ks), "graph": graph is not None},
+        "active_weight_bytes_per_token": int(active_bytes),
+        "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
+        "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "build_s": round(t_build, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    if graph is not None:
+        ctx.graph_destroy(graph)
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -361,14 +361,19 @@ def decode_stack(cfg: LayerCfg, layers: list, hidden, Ks: list, Vs: list, kv_len
     return traces, ov
 
 
-def rel_err(got, ref) -> float:
+def rel_err(got, ref, floor_frac: float = 0.01) -> float:
     """Output error measure used by the parity tests:
-    max_i |got_i - ref_i| / max(|ref_i|, 0.01 * rms(ref))."""
+    max_i |got_i - ref_i| / max(|ref_i|, floor_frac * rms(ref)).
+
+    floor_frac = 0.01 judges a single operator fed with bit-identical inputs.  Stages deep
+    inside a layer see inputs that already differ from the oracle's in the last fp16 bit of
+    a few elements; that perturbation reaches every output as an absolute error
+    proportional to rms(ref), so chained stages are judged with floor_frac = 1."""
     got = np.asarray(got, dtype=np.float64).ravel()
     ref = np.asarray(ref, dtype=np.float64).ravel()
     if ref.size == 0:
         return 0.0
-    floor = 0.01 * np.sqrt(np.mean(ref * ref))
+    floor = floor_frac * np.sqrt(np.mean(ref * ref))
     den = np.maximum(np.abs(ref), floor)
     den = np.where(den == 0, 1.0, den)
     return float(np.max(np.abs(got - ref) / den))

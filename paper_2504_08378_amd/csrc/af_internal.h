@@ -84,4 +84,34 @@ struct af_gemv_args {
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);
 
+// ---- cross-workgroup hand-off without cache-wide fences ------------------------------------
+// Partial results travel between workgroups (possibly on different XCDs, each with its own
+// L2) through agent-scope relaxed atomics: such a store is written through to memory, such a
+// load does not hit a stale L2 line.  A full agent-scope fence would write back and invalidate
+// the whole L2 of the XCD on every call, which serialises thousands of workgroups.
+// Protocol: every thread stores its partials with af_store_agent, waits for its own stores
+// (af_stores_done), the workgroup barriers, one thread takes a ticket; the workgroup whose
+// ticket is the last one reads all partials with af_load_agent.
+#ifdef __HIPCC__
+__device__ __forceinline__ void af_store_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float af_load_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void af_stores_done() {
+  // Keep the compiler from moving the stores, then wait until this wave's vector memory
+  // operations (gfx9 counts stores in vmcnt) have been acknowledged: s_waitcnt vmcnt(0) with
+  // expcnt and lgkmcnt left at their maxima (gfx9 encoding 0x0F70).
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+__device__ __forceinline__ void af_ticket_reset(int* t) {
+  __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int af_ticket_take(int* t) {
+  return __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+#endif
+
 static inline size_t af_align(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }

@@ -169,28 +169,25 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < Q4_WAVES; ++w) v += s_red[w][c];
-    mine[tile0 + c] = v;
+    af_store_agent(mine + tile0 + c, v);
   }
-  __threadfence();
+  af_stores_done();
   __syncthreads();
   if (tid == 0) {
-    int old = __hip_atomic_fetch_add(&p.tickets[blockIdx.x], 1, __ATOMIC_ACQ_REL,
-                                     __HIP_MEMORY_SCOPE_AGENT);
+    int old = af_ticket_take(&p.tickets[blockIdx.x]);
     s_last = (old == S - 1);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   for (int c = tid; c < TW; c += Q4_THREADS) {
     if (tile0 + c < p.out) {
       float v = 0.f;
       for (int q = 0; q < S; ++q)
-        v += __hip_atomic_load(p.partials + (size_t)q * p.out_pad + tile0 + c, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        v += af_load_agent(p.partials + (size_t)q * p.out_pad + tile0 + c);
       q4_store_out(p, tile0 + c, v);
     }
   }
-  if (tid == 0) p.tickets[blockIdx.x] = 0;
+  if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
 template <int LX, int U>

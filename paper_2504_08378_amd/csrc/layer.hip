@@ -172,42 +172,40 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
     if (KS == 1) {
       p.out[(size_t)h * HD + tid] = (half_t)(v / l);
     } else {
-      mine[2 + tid] = v;
+      af_store_agent(mine + 2 + tid, v);
     }
   }
   if (KS == 1) return;
   if (tid == 0) {
-    mine[0] = m;
-    mine[1] = l;
+    af_store_agent(mine, m);
+    af_store_agent(mine + 1, l);
   }
-  __threadfence();
+  af_stores_done();
   __syncthreads();
   if (tid == 0) {
-    int old = __hip_atomic_fetch_add(&p.tickets[h], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    int old = af_ticket_take(&p.tickets[h]);
     s_last = (old == KS - 1);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   // combine the splits in order
   const float* base = p.part + (size_t)h * KS * (HD + 2);
   float M = -INFINITY;
   for (int q2 = 0; q2 < KS; ++q2)
-    M = fmaxf(M, __hip_atomic_load(base + (size_t)q2 * (HD + 2), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT));
+    M = fmaxf(M, af_load_agent(base + (size_t)q2 * (HD + 2)));
   if (tid < HD) {
     float L = 0.f, v = 0.f;
     for (int q2 = 0; q2 < KS; ++q2) {
       const float* pp = base + (size_t)q2 * (HD + 2);
-      const float ms = __hip_atomic_load(pp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const float ms = af_load_agent(pp);
       if (ms == -INFINITY) continue;  // an empty split
       const float wgt = expf(ms - M);
-      L += wgt * __hip_atomic_load(pp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      v += wgt * __hip_atomic_load(pp + 2 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      L += wgt * af_load_agent(pp + 1);
+      v += wgt * af_load_agent(pp + 2 + tid);
     }
     p.out[(size_t)h * HD + tid] = (half_t)(v / L);
   }
-  if (tid == 0) p.tickets[h] = 0;
+  if (tid == 0) af_ticket_reset(&p.tickets[h]);
 }
 
 static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc,

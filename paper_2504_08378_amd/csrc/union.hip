@@ -185,27 +185,24 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < UG_WAVES; ++w) v += s_red[w][b][c];
-    mine[(size_t)b * p.out_pad + tile0 + c] = v;
+    af_store_agent(mine + (size_t)b * p.out_pad + tile0 + c, v);
   }
-  __threadfence();
+  af_stores_done();
   __syncthreads();
   if (tid == 0) {
-    int old = __hip_atomic_fetch_add(&p.tickets[blockIdx.x], 1, __ATOMIC_ACQ_REL,
-                                     __HIP_MEMORY_SCOPE_AGENT);
+    int old = af_ticket_take(&p.tickets[blockIdx.x]);
     s_last = (old == S - 1);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   for (int e = tid; e < NB * TW; e += UG_THREADS) {
     const int b = e / TW, c = e % TW;
     float v = 0.f;
     for (int q = 0; q < S; ++q)
-      v += __hip_atomic_load(p.partials + ((size_t)q * NB + b) * p.out_pad + tile0 + c,
-                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      v += af_load_agent(p.partials + ((size_t)q * NB + b) * p.out_pad + tile0 + c);
     store(b, tile0 + c, v);
   }
-  if (tid == 0) p.tickets[blockIdx.x] = 0;
+  if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
 extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,

@@ -28,7 +28,7 @@ def select_cfg(mode, k=(0, 0, 0, 0), t=(0.0, 0.0, 0.0, 0.0), reuse_mask=0) -> B.
 
 class DeviceLayer:
     """Packed weights of one layer.  `host` maps Wq, Wk, Wv, Wo, Wgate, Wup, Wdown (fp16
-    [out][in] NumPy arrays) and g_attn, g_ffn."""
+    [out][in] NumPy arrays or torch tensors) and g_attn, g_ffn."""
 
     def __init__(self, ctx: B.Context, shape, host: dict, weight_kind=B.AF_W_F16):
         self.ctx, self.shape, self.kind = ctx, shape, weight_kind
@@ -36,7 +36,8 @@ class DeviceLayer:
         nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
         dev = ctx.device
         self.keep = []
-        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        up = lambda a: (a.to(dev).contiguous() if torch.is_tensor(a)
+                        else torch.from_numpy(np.ascontiguousarray(a)).to(dev))
 
         def fused(parts, n_in):
             ld = sum(p.shape[0] for p in parts)
@@ -115,8 +116,9 @@ class DeviceStack:
         self.layers = layers
         self.n_layers = len(layers)
         dev = ctx.device
-        self.K = [torch.from_numpy(k).to(dev) for k, _ in kv]
-        self.V = [torch.from_numpy(v).to(dev) for _, v in kv]
+        up = lambda a: a.to(dev) if torch.is_tensor(a) else torch.from_numpy(a).to(dev)
+        self.K = [up(k) for k, _ in kv]
+        self.V = [up(v) for _, v in kv]
         self.kv_cap = kv_cap
         self.sets = [IdxSetBuffers(ctx, shape) for _ in layers]
         self.cfg = layer_cfg(shape, weight_kind)

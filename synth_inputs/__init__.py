@@ -22,6 +22,8 @@ from .generators import (  # noqa: F401
     ModelShape,
     activation,
     channel_scales,
+    device_kv_cache,
+    device_layer_weights,
     kv_cache,
     layer_weights,
     norm_gain,

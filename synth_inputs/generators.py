@@ -133,3 +133,45 @@ def layer_weights(seed: int, shape: ModelShape, layer: int, threads: int = 1) ->
         "g_attn": norm_gain(seed, d, shape.name, layer, "attn"),
         "g_ffn": norm_gain(seed, d, shape.name, layer, "ffn"),
     }
+
+
+def device_layer_weights(seed: int, shape: ModelShape, layer: int, device="cuda") -> dict:
+    """Same tensors as layer_weights(), drawn on the GPU with torch's seeded generator (a
+    different random stream, same distribution) so that multi-GB stacks are ready in
+    seconds.  Returns out-major fp16 torch tensors; callers that need the values on the
+    host copy them back."""
+    import torch
+
+    d, f, hd = shape.d_model, shape.d_ffn, shape.head_dim
+    nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
+    gen = torch.Generator(device=device)
+
+    def mk(name, o, i):
+        gen.manual_seed((int(seed) * 1000003 + zlib.crc32(f"{shape.name}/{layer}/{name}".encode())) & 0x7FFFFFFFFFFFFFFF)
+        w = torch.randn((o, i), generator=gen, device=device, dtype=torch.float32)
+        return (w * 0.02).to(torch.float16)
+
+    def gain(name):
+        gen.manual_seed((int(seed) * 1000003 + zlib.crc32(f"{shape.name}/{layer}/gain/{name}".encode())) & 0x7FFFFFFFFFFFFFFF)
+        return (1.0 + 0.02 * torch.randn(d, generator=gen, device=device, dtype=torch.float32)).to(torch.float16)
+
+    return {
+        "Wq": mk("q", nq, d), "Wk": mk("k", nkv, d), "Wv": mk("v", nkv, d), "Wo": mk("o", d, nq),
+        "Wgate": mk("gate", f, d), "Wup": mk("up", f, d), "Wdown": mk("down", d, f),
+        "g_attn": gain("attn"), "g_ffn": gain("ffn"),
+    }
+
+
+def device_kv_cache(seed: int, shape: ModelShape, layer: int, cap: int, filled: int, device="cuda"):
+    """K and V caches [n_kv][cap][hd] fp16 on the GPU, first `filled` slots ~ N(0,1)."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    out = []
+    for which in ("K", "V"):
+        gen.manual_seed((int(seed) * 1000003 + zlib.crc32(f"{shape.name}/{layer}/kv/{which}".encode())) & 0x7FFFFFFFFFFFFFFF)
+        c = torch.zeros((shape.n_kv_heads, cap, shape.head_dim), dtype=torch.float16, device=device)
+        c[:, :filled] = torch.randn((shape.n_kv_heads, filled, shape.head_dim), generator=gen,
+                                    device=device, dtype=torch.float32).to(torch.float16)
+        out.append(c)
+    return out[0], out[1]

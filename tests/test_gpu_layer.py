@@ -240,3 +240,41 @@ def test_layer_argument_errors(ctx):
     with pytest.raises(B.AfError) as e:
         st.layer(0, hin, hout, KV_LEN, KV_LEN, M.select_cfg(7))
     assert e.value.status == -1
+
+
+def test_7b_layer_full_size_stage_by_stage(ctx):
+    """One layer at the benchmark's full shape (d 4096, ffn 11008, 32 heads, 512 cached
+    keys): every stage against the oracle with the oracle's sets forced, then the GPU's own
+    selections checked from the definition."""
+    shape = S.MODEL_SHAPES["7b"]
+    kv_len, kv_cap = 512, 528
+    layers, kv, h = _host_stack(shape, 1, seed=0, kv_len=kv_len, kv_cap=kv_cap, threads=8)
+    ks = _ks(shape, 50)
+    tr = O.decode_layer(_ocfg(shape), layers[0], h, kv[0][0].copy(), kv[0][1].copy(), kv_len, kv_len,
+                        O.SelectCfg(O.SEL_TOPK, ks))
+    st = _dev_stack(ctx, shape, layers, kv, kv_cap=kv_cap)
+    st.sets[0].load(tr.idx)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    st.layer(0, hin, hout, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+    ctx.synchronize()
+    t = _taps(ctx, shape)
+    # x_qkv and qkv see the oracle's own input bits (strict floor); later stages inherit
+    # last-bit differences of their inputs and are judged against the vector's rms
+    errs = {
+        "x_qkv": O.rel_err(t["x_qkv"], tr.x[0]), "qkv": O.rel_err(t["qkv"], tr.qkv),
+        "attn": O.rel_err(t["attn"], tr.attn, 1.0), "h_mid": O.rel_err(t["h_mid"], tr.h_mid, 1.0),
+        "x_gateup": O.rel_err(t["x_gateup"], tr.x[2], 1.0), "gateup": O.rel_err(t["gateup"], tr.gateup, 1.0),
+        "x_down": O.rel_err(t["x_down"], tr.x[3], 1.0) / 2, "hidden": O.rel_err(to_host(hout), tr.hidden, 1.0),
+    }
+    print("stage errors:", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert max(errs.values()) <= TOL, errs
+    # own selection at full width
+    st.layer(0, hin, hout, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks))
+    ctx.synchronize()
+    t = _taps(ctx, shape)
+    xs = (t["x_qkv"], t["attn"], t["x_gateup"], t["x_down"])
+    assert np.array_equal(st.sets[0].fetch(0, ks[0]), tr.idx[0])      # same input bits as the oracle
+    for p in range(4):
+        got = st.sets[0].fetch(p, ks[p])
+        _exact_topk_property(xs[p], got, ks[p])
+        assert _sets_close(got, tr.idx[p], tr.x[p]), p
