@@ -99,6 +99,24 @@ __device__ __forceinline__ void af_store_agent(float* p, float v) {
 __device__ __forceinline__ float af_load_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Sum of S partials p[0], p[stride], ... in index order, with up to 16 loads in flight.
+__device__ __forceinline__ float af_sum_partials(const float* p, size_t stride, int S) {
+  float v = 0.f;
+  int q = 0;
+  for (; q + 16 <= S; q += 16) {
+    float t[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) t[u] = af_load_agent(p + (size_t)(q + u) * stride);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v += t[u];
+  }
+  float t[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) t[u] = (q + u < S) ? af_load_agent(p + (size_t)(q + u) * stride) : 0.f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) v += t[u];
+  return v;
+}
 __device__ __forceinline__ void af_stores_done() {
   // Keep the compiler from moving the stores, then wait until this wave's vector memory
   // operations (gfx9 counts stores in vmcnt) have been acknowledged: s_waitcnt vmcnt(0) with

@@ -139,10 +139,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_f16_kernel(GemvParams p) {
   if (!s_last) return;
   for (int c = tid; c < TW; c += GEMV_THREADS) {
     if (tile0 + c < p.out) {
-      float v = 0.f;
-      for (int q = 0; q < S; ++q)
-        v += af_load_agent(p.partials + (size_t)q * p.out_pad + tile0 + c);
-      store_out(p, tile0 + c, v);
+      store_out(p, tile0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
     }
   }
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
@@ -159,10 +156,11 @@ static void launch_variant(bool has_idx, dim3 grid, hipStream_t st, const GemvPa
 // Tile width and split count for a shape.  AF_GEMV_LX / AF_GEMV_SPLIT / AF_GEMV_WGS in the
 // environment override the heuristic (used by the tuning sweeps of the benchmark).
 static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int* s_out) {
-  int lx = 64;
-  if (out <= 2048) lx = 16;
-  else if (out <= 8192) lx = 32;
-  int target_wgs = ctx->n_cu * 8;
+  // Measured on the 7B operators (cold matrices): 128-column tiles (256 B per row and
+  // workgroup) win up to ~16K columns, 256-column tiles beyond; narrow outputs want about one
+  // workgroup per CU (long row loops, few partials), wide ones about four.
+  int lx = out <= 16384 ? 16 : 32;
+  int target_wgs = out <= 4096 ? ctx->n_cu : ctx->n_cu * 4;
   if (const char* e = getenv("AF_GEMV_LX")) {
     int v = atoi(e);
     if (v == 16 || v == 32 || v == 64) lx = v;

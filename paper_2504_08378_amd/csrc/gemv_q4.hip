@@ -181,10 +181,7 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
   if (!s_last) return;
   for (int c = tid; c < TW; c += Q4_THREADS) {
     if (tile0 + c < p.out) {
-      float v = 0.f;
-      for (int q = 0; q < S; ++q)
-        v += af_load_agent(p.partials + (size_t)q * p.out_pad + tile0 + c);
-      q4_store_out(p, tile0 + c, v);
+      q4_store_out(p, tile0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
     }
   }
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);

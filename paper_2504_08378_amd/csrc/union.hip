@@ -197,10 +197,8 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
   if (!s_last) return;
   for (int e = tid; e < NB * TW; e += UG_THREADS) {
     const int b = e / TW, c = e % TW;
-    float v = 0.f;
-    for (int q = 0; q < S; ++q)
-      v += af_load_agent(p.partials + ((size_t)q * NB + b) * p.out_pad + tile0 + c);
-    store(b, tile0 + c, v);
+    store(b, tile0 + c,
+          af_sum_partials(p.partials + (size_t)b * p.out_pad + tile0 + c, (size_t)NB * p.out_pad, S));
   }
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
