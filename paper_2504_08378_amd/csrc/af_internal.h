@@ -69,14 +69,31 @@ struct af_select_args {
 };
 int af_launch_select(af_ctx* ctx, int producer, const af_select_args& a);
 
+enum { AF_ROWS_GIVEN = 3 };  // rows come from memory (idx list) or are all channels (dense)
+
+// Where a fused GEMV gets its input vector and its rows from (see row_prologue.h).
+struct af_row_src {
+  int pro;              // AF_PRO_NONE | AF_PRO_RMSNORM | AF_PRO_SILUMUL
+  const half_t* src;    // NONE: x[n]; RMSNORM: hidden[n]; SILUMUL: gate|up [2n]
+  const half_t* gain;   // RMSNORM
+  float eps;
+  half_t* x_out;        // produced x is also stored here (null: not stored)
+  int n;
+  int sel;              // AF_SEL_TOPK | AF_SEL_THRESHOLD | AF_ROWS_GIVEN
+  int k;
+  float t;
+  const int32_t* idx;   // AF_ROWS_GIVEN: list (null = dense)
+  int nidx_host;
+  const int32_t* nidx_dev;
+  int32_t* idx_out;     // selection result (null: not stored)
+  int32_t* count_out;
+};
+
 struct af_gemv_args {
   const void* W;          // fp16 in-major, or packed nibbles
   const half_t* scales;   // q4 only
   int in, out, ld;
-  const half_t* x;
-  const int32_t* idx;     // null = dense
-  int nidx_host;
-  const int32_t* nidx_dev;
+  af_row_src rows;
   void* y;
   int y_kind;
   const half_t* residual;

@@ -8,27 +8,29 @@
 // LX lanes span the tile (16 bytes = 8 columns per lane, one global_load_dwordx4) and the
 // remaining 64/LX lane groups take different rows, so one wave instruction fetches 64/LX
 // rows x (16*LX) contiguous bytes.  The row loop is unrolled U deep to keep U independent
-// 16-byte loads per lane in flight.  idx[t] and x[idx[t]] of the split are staged in LDS
-// first, so the weight addresses never wait on a dependent global load.
+// 16-byte loads per lane in flight.  The rows of the split are staged in LDS first as
+// (index, x) pairs, so the weight addresses never wait on a dependent global load.
+// Front end (row_prologue.h): the kernel can build its input vector itself (RMSNorm of the
+// residual stream, SiLU(gate)*up) and run the top-k / threshold selection on it, each
+// workgroup for itself, which removes the separate selection kernels from a decoder layer.
 // Reduction: lane groups by wave shuffles, waves through LDS, splits through an fp32
 // partials buffer; the workgroup that arrives last at a tile's ticket adds the S partials in
 // split order, so the result does not depend on scheduling.
 #include "af_internal.h"
+#include "row_prologue.h"
 
 #define GEMV_THREADS 256
 #define GEMV_WAVES (GEMV_THREADS / AF_WAVE)
-#define GEMV_CHUNK 1024  // staged (idx, x) pairs per pass
+#define GEMV_LIST 2048  // staged rows per pass: (index << 16 | fp16 bits of x)
 
 struct GemvParams {
   const half_t* W;
-  const half_t* x;
-  const int32_t* idx;
-  const int32_t* nidx_dev;
+  af_row_src rows;
   float* partials;
   int* tickets;
   void* y;
   const half_t* residual;
-  int out, ld, nidx_host, y_kind, out_pad;
+  int out, ld, y_kind, out_pad, use_lds_x;
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
@@ -39,64 +41,85 @@ __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v)
     reinterpret_cast<float*>(p.y)[col] = v;
 }
 
-template <int LX, int U, bool HAS_IDX>
+template <int LX, int U>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_f16_kernel(GemvParams p) {
   constexpr int LY = AF_WAVE / LX;
   constexpr int TW = LX * 8;
   constexpr int STEP = GEMV_WAVES * LY;  // rows taken per workgroup iteration
-  __shared__ int s_idx[GEMV_CHUNK];
-  __shared__ float s_x[GEMV_CHUNK];
-  __shared__ float s_red[GEMV_WAVES][TW];
+  typedef RowPrologue<GEMV_THREADS> RP;
+  extern __shared__ __align__(16) unsigned short xs[];  // the operator input, when built here
+  __shared__ unsigned s_scratch[RP_SCRATCH_WORDS]; // histograms, later the wave sums
+  __shared__ unsigned s_list[GEMV_LIST];
+  __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
+  float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
+  static_assert(GEMV_WAVES * TW <= RP_SCRATCH_WORDS, "wave sums must fit the scratch area");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
   const int col = blockIdx.x * TW + lx * 8;
   const int col_ld = col < p.out ? col : 0;  // lanes past the edge read column 0 and are dropped
   const int S = gridDim.y, s = blockIdx.y;
+  const af_row_src& r = p.rows;
 
-  int nidx = p.nidx_host;
-  if (p.nidx_dev) nidx = min(*p.nidx_dev, nidx);
-  const int R = (nidx + S - 1) / S;
-  const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+  if (p.use_lds_x) RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x);
 
   float acc[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   const half_t* wcol = p.W + col_ld;
 
-  for (int base = r0; base < r1; base += GEMV_CHUNK) {
-    const int cnt = min(GEMV_CHUNK, r1 - base);
-    __syncthreads();
-    for (int i = tid; i < cnt; i += GEMV_THREADS) {
-      int j = HAS_IDX ? p.idx[base + i] : base + i;
-      s_idx[i] = j;
-      s_x[i] = (float)p.x[j];
-    }
-    __syncthreads();
+  // One pass over `cnt` staged rows of s_list.
+  auto stream = [&](int cnt) {
     int i = wave * LY + ly;
     for (; i + (U - 1) * STEP < cnt; i += U * STEP) {
       half8 w[U];
-      float xv[U];
+      unsigned e[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int j = s_idx[i + u * STEP];
-        xv[u] = s_x[i + u * STEP];
-        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)j * p.ld);
+        e[u] = s_list[i + u * STEP];
+        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u) {
+        const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e[u] & 0xFFFFu));
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv[u];
+        for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv;
+      }
     }
     for (; i < cnt; i += STEP) {
-      const int j = s_idx[i];
-      const float xv = s_x[i];
-      half8 w = *reinterpret_cast<const half8*>(wcol + (size_t)j * p.ld);
+      const unsigned e = s_list[i];
+      const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu));
+      const half8 w = *reinterpret_cast<const half8*>(wcol + (size_t)(e >> 16) * p.ld);
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[c] += (float)w[c] * xv;
     }
+  };
+
+  if (r.sel != AF_ROWS_GIVEN) {
+    int nidx_total;
+    const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
+                                     blockIdx.x == 0 && s == 0, &nidx_total);
+    stream(cnt);
+  } else {
+    int nidx = r.nidx_host;
+    if (r.nidx_dev) nidx = min(*r.nidx_dev, nidx);
+    const int R = (nidx + S - 1) / S;
+    const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+    const unsigned short* xg = reinterpret_cast<const unsigned short*>(r.src);
+    for (int base = r0; base < r1; base += GEMV_LIST) {
+      const int cnt = min(GEMV_LIST, r1 - base);
+      __syncthreads();
+      for (int i = tid; i < cnt; i += GEMV_THREADS) {
+        const int j = r.idx ? r.idx[base + i] : base + i;
+        const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
+        s_list[i] = ((unsigned)j << 16) | bits;
+      }
+      __syncthreads();
+      stream(cnt);
+    }
   }
+  __syncthreads();  // s_scratch changes its role: histograms -> wave sums
 
   // lane groups -> one row of sums per wave
 #pragma unroll
@@ -145,16 +168,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_f16_kernel(GemvParams p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
 }
 
-template <int LX, int U>
-static void launch_variant(bool has_idx, dim3 grid, hipStream_t st, const GemvParams& p) {
-  if (has_idx)
-    hipLaunchKernelGGL((gemv_f16_kernel<LX, U, true>), grid, dim3(GEMV_THREADS), 0, st, p);
-  else
-    hipLaunchKernelGGL((gemv_f16_kernel<LX, U, false>), grid, dim3(GEMV_THREADS), 0, st, p);
-}
-
 // Tile width and split count for a shape.  AF_GEMV_LX / AF_GEMV_SPLIT / AF_GEMV_WGS in the
-// environment override the heuristic (used by the tuning sweeps of the benchmark).
+// environment override the heuristic (used by tuning sweeps).
 static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int* s_out) {
   // Measured on the 7B operators (cold matrices): 128-column tiles (256 B per row and
   // workgroup) win up to ~16K columns, 256-column tiles beyond; narrow outputs want about one
@@ -170,7 +185,7 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int
     if (v > 0) target_wgs = v;
   }
   const int tiles = (out + lx * 8 - 1) / (lx * 8);
-  int S = (target_wgs + tiles - 1) / tiles;
+  int S = target_wgs / tiles;  // never more workgroups than the chip holds at once
   if (const char* e = getenv("AF_GEMV_SPLIT")) {
     int v = atoi(e);
     if (v > 0) S = v;
@@ -186,35 +201,53 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int
 }
 
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
+  const af_row_src& r = a.rows;
+  // the largest index set this launch can meet (the count of a threshold set is only known
+  // on the device)
+  int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
   int lx, S;
-  choose_config(ctx, a.out, a.nidx_host, &lx, &S);
+  choose_config(ctx, a.out, max_rows, &lx, &S);
   const int tw = lx * 8;
   const int tiles = (a.out + tw - 1) / tw;
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
+  // a selecting workgroup keeps its whole split in the staged list
+  if (r.sel != AF_ROWS_GIVEN) {
+    const int need = (max_rows + GEMV_LIST - 1) / GEMV_LIST;
+    if (S < need) S = need;
+  }
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
+  if (r.sel != AF_ROWS_GIVEN && (size_t)S * GEMV_LIST < (size_t)max_rows) return AF_EWORKSPACE;
   GemvParams p;
   p.W = (const half_t*)a.W;
-  p.x = a.x;
-  p.idx = a.idx;
-  p.nidx_dev = a.nidx_dev;
+  p.rows = r;
   p.partials = (float*)(ctx->ws + ctx->lay.partials);
   p.tickets = (int*)(ctx->ws + ctx->lay.tickets);
   p.y = a.y;
   p.residual = a.residual;
   p.out = a.out;
   p.ld = a.ld;
-  p.nidx_host = a.nidx_host;
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
-  dim3 grid(tiles, S);
-  const bool has_idx = a.idx != nullptr;
+  p.use_lds_x = (r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN) ? 1 : 0;
+  const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
+  static bool attr_done = false;
+  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
+    attr_done = true;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<16, 8>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<32, 8>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<64, 8>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+  }
+  dim3 grid(tiles, S), block(GEMV_THREADS);
   if (lx == 64)
-    launch_variant<64, 8>(has_idx, grid, ctx->stream, p);
+    hipLaunchKernelGGL((gemv_f16_kernel<64, 8>), grid, block, lds, ctx->stream, p);
   else if (lx == 32)
-    launch_variant<32, 8>(has_idx, grid, ctx->stream, p);
+    hipLaunchKernelGGL((gemv_f16_kernel<32, 8>), grid, block, lds, ctx->stream, p);
   else
-    launch_variant<16, 8>(has_idx, grid, ctx->stream, p);
+    hipLaunchKernelGGL((gemv_f16_kernel<16, 8>), grid, block, lds, ctx->stream, p);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }
@@ -239,10 +272,13 @@ extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
   a.in = in;
   a.out = out;
   a.ld = ld;
-  a.x = (const half_t*)x_f16;
-  a.idx = idx;
-  a.nidx_host = nidx_host;
-  a.nidx_dev = nidx_dev;
+  a.rows.pro = AF_PRO_NONE;
+  a.rows.src = (const half_t*)x_f16;
+  a.rows.n = in;
+  a.rows.sel = AF_ROWS_GIVEN;
+  a.rows.idx = idx;
+  a.rows.nidx_host = nidx_host;
+  a.rows.nidx_dev = nidx_dev;
   a.y = y;
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;

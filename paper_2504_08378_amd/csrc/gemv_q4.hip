@@ -211,7 +211,8 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
     if (v > 0) target = v;
   }
   int S = (target + tiles - 1) / tiles;
-  int max_s = (a.nidx_host + 63) / 64;
+  if (a.rows.pro != AF_PRO_NONE || a.rows.sel != AF_ROWS_GIVEN) return AF_EINVAL;  // no fused front end yet
+  int max_s = (a.rows.nidx_host + 63) / 64;
   if (max_s < 1) max_s = 1;
   if (S > max_s) S = max_s;
   if (S > 256) S = 256;
@@ -219,20 +220,20 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   Q4Params p;
   p.packed = (const unsigned char*)a.W;
   p.scales = a.scales;
-  p.x = a.x;
-  p.idx = a.idx;
-  p.nidx_dev = a.nidx_dev;
+  p.x = a.rows.src;
+  p.idx = a.rows.idx;
+  p.nidx_dev = a.rows.nidx_dev;
   p.partials = (float*)(ctx->ws + ctx->lay.partials);
   p.tickets = (int*)(ctx->ws + ctx->lay.tickets);
   p.y = a.y;
   p.residual = a.residual;
   p.out = a.out;
   p.ld = a.ld;
-  p.nidx_host = a.nidx_host;
+  p.nidx_host = a.rows.nidx_host;
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
   dim3 grid(tiles, S);
-  const bool has_idx = a.idx != nullptr;
+  const bool has_idx = a.rows.idx != nullptr;
   if (lx == 64)
     launch_q4<64, 8>(has_idx, grid, ctx->stream, p);
   else if (lx == 32)
@@ -264,10 +265,13 @@ extern "C" int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* sc
   a.in = in;
   a.out = out;
   a.ld = ld;
-  a.x = (const half_t*)x_f16;
-  a.idx = idx;
-  a.nidx_host = nidx_host;
-  a.nidx_dev = nidx_dev;
+  a.rows.pro = AF_PRO_NONE;
+  a.rows.src = (const half_t*)x_f16;
+  a.rows.n = in;
+  a.rows.sel = AF_ROWS_GIVEN;
+  a.rows.idx = idx;
+  a.rows.nidx_host = nidx_host;
+  a.rows.nidx_dev = nidx_dev;
   a.y = y;
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;

@@ -3,16 +3,15 @@
 // linear operator and the gathered GEMV (operation C) behind it; Section 3's reuse of a
 // group leader's index sets is a bit mask over the four selection points.
 //
-// Launch sequence of one layer (all on the context's stream, no host synchronisation):
-//   1 rmsnorm(hidden) [+ select]      -> x_qkv, idx0        one workgroup
-//   2 gemv  Wqkv                      -> qkv
-//   3 rope + kv append + attention    -> attn               (heads x key splits) workgroups
-//   4 select(attn)                    -> idx1
-//   5 gemv  Wo + hidden               -> h_mid
-//   6 rmsnorm(h_mid) [+ select]       -> x_gateup, idx2
-//   7 gemv  Wgateup                   -> gateup
-//   8 silu(gate)*up [+ select]        -> x_down, idx3
-//   9 gemv  Wdown + h_mid             -> hidden_out
+// Launch sequence of one layer (all on the context's stream, no host synchronisation); with
+// fp16 weights the norm / SwiGLU producers and the selections run inside the GEMV kernels'
+// front end, so a layer is five launches:
+//   1 gemv  Wqkv     on rmsnorm(hidden), selecting        -> x_qkv, idx0, qkv
+//   2 rope + kv append + attention                        -> attn
+//   3 gemv  Wo       on attn, selecting, + hidden         -> idx1, h_mid
+//   4 gemv  Wgateup  on rmsnorm(h_mid), selecting         -> x_gateup, idx2, gateup
+//   5 gemv  Wdown    on silu(gate)*up, selecting, + h_mid -> x_down, idx3, hidden_out
+// (4-bit weights still use the separate selection kernels of select.hip before each GEMV.)
 #include <math.h>
 
 #include "af_internal.h"
@@ -300,6 +299,7 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
     }
   }
 
+  // Separate selection kernel (used where the GEMV has no fused front end: 4-bit weights).
   auto select_at = [&](int p, int producer, const half_t* src_v, const half_t* gain,
                        half_t* x_out) -> int {
     af_select_args a{};
@@ -314,38 +314,70 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
     a.t = sel->t[p];
     a.idx = own->idx[p];
     a.count = own->count[p];
-    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;  // nothing to do
     if (a.mode == AF_SEL_TOPK && a.k == 0) a.mode = AF_SEL_DENSE;         // empty set
-    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;
+    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;  // nothing to do
     return af_launch_select(ctx, producer, a);
   };
-  auto gemv = [&](int p, const void* W, const void* Sc, int in, int out, const half_t* x,
-                  half_t* y, const half_t* res) -> int {
+  // GEMV at selection point p.  fused: the kernel builds x from `src_v` (producer) and selects
+  // for itself; otherwise x is ready in `x` and the rows come from pt[p].
+  auto gemv = [&](int p, const void* W, const void* Sc, int in, int out, int producer,
+                  const half_t* src_v, const half_t* gain, half_t* x, half_t* y,
+                  const half_t* res) -> int {
     af_gemv_args a{};
     a.W = W;
     a.scales = (const half_t*)Sc;
     a.in = in;
     a.out = out;
     a.ld = out;
-    a.x = x;
-    a.idx = pt[p].idx;
-    a.nidx_host = pt[p].nidx_host;
-    a.nidx_dev = pt[p].nidx_dev;
     a.y = y;
     a.y_kind = AF_F16;
     a.residual = res;
-    return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a);
+    af_row_src& r = a.rows;
+    r.n = in;
+    r.eps = cfg->rms_eps;
+    const bool reused = (reuse >> p) & 1u;
+    const bool selects = !reused && sel->mode != AF_SEL_DENSE;
+    if (q4) {
+      int rc2 = select_at(p, producer, src_v, gain, x);
+      if (rc2) return rc2;
+      r.pro = AF_PRO_NONE;
+      r.src = producer == AF_PRO_NONE ? src_v : x;
+      r.sel = AF_ROWS_GIVEN;
+      r.idx = pt[p].idx;
+      r.nidx_host = pt[p].nidx_host;
+      r.nidx_dev = pt[p].nidx_dev;
+      return af_launch_gemv_q4(ctx, a);
+    }
+    r.pro = producer;
+    r.src = src_v;
+    r.gain = gain;
+    r.x_out = x;
+    if (selects) {
+      r.sel = sel->mode;
+      r.k = sel->k[p];
+      r.t = sel->t[p];
+      r.idx_out = own->idx[p];
+      r.count_out = own->count[p];
+    } else {
+      r.sel = AF_ROWS_GIVEN;
+      r.idx = pt[p].idx;
+      r.nidx_host = pt[p].nidx_host;
+      r.nidx_dev = pt[p].nidx_dev;
+    }
+    return af_launch_gemv_f16(ctx, a);
   };
 
-  if ((rc = select_at(0, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0))) return rc;
-  if ((rc = gemv(0, w->Wqkv, w->Sqkv, d, qkv_out, x0, qkv, nullptr))) return rc;
+  if ((rc = gemv(0, w->Wqkv, w->Sqkv, d, qkv_out, AF_PRO_RMSNORM, h_in,
+                 (const half_t*)w->g_attn_norm, x0, qkv, nullptr)))
+    return rc;
   if ((rc = launch_attention(ctx, cfg, qkv, kc, vc, kv_len, kv_cap, pos, attn))) return rc;
-  if ((rc = select_at(1, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
-  if ((rc = gemv(1, w->Wo, w->So, qdim, d, attn, hmid, h_in))) return rc;
-  if ((rc = select_at(2, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2))) return rc;
-  if ((rc = gemv(2, w->Wgateup, w->Sgateup, d, 2 * f, x2, gu, nullptr))) return rc;
-  if ((rc = select_at(3, AF_PRO_SILUMUL, gu, nullptr, x3))) return rc;
-  if ((rc = gemv(3, w->Wdown, w->Sdown, f, d, x3, h_out, hmid))) return rc;
+  if ((rc = gemv(1, w->Wo, w->So, qdim, d, AF_PRO_NONE, attn, nullptr, nullptr, hmid, h_in)))
+    return rc;
+  if ((rc = gemv(2, w->Wgateup, w->Sgateup, d, 2 * f, AF_PRO_RMSNORM, hmid,
+                 (const half_t*)w->g_ffn_norm, x2, gu, nullptr)))
+    return rc;
+  if ((rc = gemv(3, w->Wdown, w->Sdown, f, d, AF_PRO_SILUMUL, gu, nullptr, x3, h_out, hmid)))
+    return rc;
   return AF_OK;
 }
 

@@ -1,0 +1,284 @@
+// Workgroup-local front end of the fused GEMV kernels: produce the operator's input vector in
+// LDS (plain copy, RMSNorm, or SiLU(gate)*up) and, when asked, run the activation selection
+// (Section 2.1 Top-K sparsity / Section 6 threshold form; Section 4 operation T) right there,
+// so that operation T needs no kernel of its own: every workgroup of the GEMV repeats the
+// cheap O(n) selection on its own copy of the vector and keeps only its split of the
+// ascending index list.  The arithmetic is the same as in select.hip (exact two-digit radix
+// select on the 15-bit magnitude key, ties to the lower index).
+#pragma once
+#include "af_internal.h"
+
+#define RP_HIST_COPIES 8
+#define RP_SCRATCH_WORDS (384 * RP_HIST_COPIES)  // 12 KB: both digit tables; reused by the caller afterwards
+
+template <int THREADS>
+struct RowPrologue {
+  static constexpr int WAVES = THREADS / AF_WAVE;
+
+  struct Smem {
+    unsigned merged[256];
+    unsigned wave_tot[WAVES];
+    float red[WAVES];
+    unsigned digit, above, total;
+  };
+
+  // Fill xs[0..n) with the fp16 bits of the operator input (n % 8 == 0).  Global reads are
+  // 16-byte vectors issued four at a time, so a thread waits for memory once per batch and
+  // not once per element.
+  static __device__ __forceinline__ void produce(const af_row_src& r, unsigned short* xs, Smem& sm,
+                                                 bool store_x, int store_phase, int store_stride) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = r.n, nvec = n >> 3;
+    constexpr int B = 4;
+    half8* xv = reinterpret_cast<half8*>(xs);
+    const half8* src = reinterpret_cast<const half8*>(r.src);
+    half8 zero;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) zero[c] = (half_t)0;
+    if (r.pro == AF_PRO_NONE) {
+      for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
+        half8 t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+          if (v0 + u * THREADS < nvec) xv[v0 + u * THREADS] = t[u];
+      }
+    } else if (r.pro == AF_PRO_RMSNORM) {
+      const half8* gain = reinterpret_cast<const half8*>(r.gain);
+      float ss = 0.f;
+      for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
+        half8 t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) ss += (float)t[u][c] * (float)t[u][c];
+          if (v0 + u * THREADS < nvec) xv[v0 + u * THREADS] = t[u];  // raw; normalised below
+        }
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, AF_WAVE);
+      if (lane == 0) sm.red[wave] = ss;
+      __syncthreads();
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) tot += sm.red[w];
+      const float scale = 1.0f / sqrtf(tot / (float)n + r.eps);
+      for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
+        half8 g[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) g[u] = (v0 + u * THREADS < nvec) ? gain[v0 + u * THREADS] : zero;
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          if (v0 + u * THREADS < nvec) {
+            half8 h = xv[v0 + u * THREADS];   // each thread revisits the vectors it wrote
+#pragma unroll
+            for (int c = 0; c < 8; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
+            xv[v0 + u * THREADS] = h;
+          }
+        }
+      }
+    } else {  // AF_PRO_SILUMUL: src = gate[n] | up[n]
+      const half8* up = reinterpret_cast<const half8*>(r.src + n);
+      for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
+        half8 g[B], u8[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          const bool ok = v0 + u * THREADS < nvec;
+          g[u] = ok ? src[v0 + u * THREADS] : zero;
+          u8[u] = ok ? up[v0 + u * THREADS] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          if (v0 + u * THREADS < nvec) {
+            half8 h;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              const float gg = (float)g[u][c];
+              h[c] = (half_t)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * (float)u8[u][c]);
+            }
+            xv[v0 + u * THREADS] = h;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (store_x && r.x_out != nullptr) {
+      half8* dst = reinterpret_cast<half8*>(r.x_out);
+      for (int v = store_phase * THREADS + tid; v < nvec; v += store_stride * THREADS) dst[v] = xv[v];
+    }
+  }
+
+  // Histogram scratch: RP_HIST_COPIES replicas, replica-major (replica r of bin b at
+  // r * 256 + b): lanes of one replica that hit different bins hit different banks, and the
+  // merge reads 256 consecutive words per replica.  First 256-bin table at word 0, the
+  // 128-bin table of the second digit behind it.
+  static constexpr int H1 = 0;
+  static constexpr int H2 = 256 * RP_HIST_COPIES;
+
+  static __device__ __forceinline__ void zero_hist(unsigned* hist) {
+    for (int i = threadIdx.x; i < RP_SCRATCH_WORDS; i += THREADS) hist[i] = 0;
+  }
+
+  // digit d with count(digit > d) < want <= count(digit >= d); result in sm.digit / sm.above
+  static __device__ __forceinline__ void find_digit(const unsigned* hist, Smem& sm, int nbins,
+                                                    unsigned want) {
+    const int tid = threadIdx.x;
+    for (int b = tid; b < 256; b += THREADS) {
+      unsigned s = 0;
+      if (b < nbins) {
+#pragma unroll
+        for (int c = 0; c < RP_HIST_COPIES; ++c) s += hist[c * nbins + b];
+      }
+      sm.merged[b] = s;
+    }
+    __syncthreads();
+    if (tid < AF_WAVE) {
+      const unsigned b0 = sm.merged[4 * tid], b1 = sm.merged[4 * tid + 1],
+                     b2 = sm.merged[4 * tid + 2], b3 = sm.merged[4 * tid + 3];
+      const unsigned mine = b0 + b1 + b2 + b3;
+      unsigned v = mine;
+#pragma unroll
+      for (int off = 1; off < AF_WAVE; off <<= 1) {
+        const unsigned o = __shfl_down(v, off, AF_WAVE);
+        if (tid + off < AF_WAVE) v += o;
+      }
+      unsigned above = v - mine;
+      const unsigned cnt[4] = {b0, b1, b2, b3};
+#pragma unroll
+      for (int q = 3; q >= 0; --q) {
+        if (above < want && want <= above + cnt[q]) {
+          sm.digit = 4 * tid + q;
+          sm.above = above;
+        }
+        above += cnt[q];
+      }
+    }
+    __syncthreads();
+  }
+
+  // exclusive prefix over the workgroup in thread order; total left in sm.total
+  static __device__ __forceinline__ unsigned excl_scan(unsigned v, Smem& sm) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned inc = v;
+#pragma unroll
+    for (int off = 1; off < AF_WAVE; off <<= 1) {
+      const unsigned o = __shfl_up(inc, off, AF_WAVE);
+      if (lane >= off) inc += o;
+    }
+    if (lane == 63) sm.wave_tot[wave] = inc;
+    __syncthreads();
+    unsigned base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const unsigned t = sm.wave_tot[w];
+      if (w < wave) base += t;
+      tot += t;
+    }
+    if (threadIdx.x == 0) sm.total = tot;
+    __syncthreads();
+    return base + inc - v;
+  }
+
+  // Select on xs[0..n) (n % 8 == 0) and keep the entries of split s of S in list[] as
+  // (index << 16 | fp16 bits).  Returns the number of entries kept by this workgroup;
+  // *nidx_total is the size of the whole index set.  `hist` is RP_SCRATCH_WORDS words of LDS.
+  // Every thread owns a contiguous run of 8-element vectors, read from LDS 16 bytes at a
+  // time in each pass; the thread order is therefore the index order.
+  static __device__ __forceinline__ int select_split(const af_row_src& r, const unsigned short* xs,
+                                                     unsigned* hist, Smem& sm, unsigned* list,
+                                                     int S, int s, bool store_idx, bool store_count,
+                                                     int* nidx_total) {
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nvec = r.n >> 3;
+    const int cv = (nvec + THREADS - 1) / THREADS;  // vectors per thread
+    const int v0 = min(tid * cv, nvec), v1 = min(v0 + cv, nvec);
+    const u16x8* xv = reinterpret_cast<const u16x8*>(xs);
+    const int rep = lane & (RP_HIST_COPIES - 1);
+    unsigned T = 0x8000u, quota = 0;
+    const bool topk = r.sel == AF_SEL_TOPK;
+    if (topk && r.k > 0) {
+      zero_hist(hist);
+      __syncthreads();
+      for (int v = v0; v < v1; ++v) {
+        const u16x8 b = xv[v];
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
+      }
+      __syncthreads();
+      find_digit(hist + H1, sm, 256, (unsigned)r.k);
+      const unsigned d1 = sm.digit, above1 = sm.above;
+      for (int v = v0; v < v1; ++v) {
+        const u16x8 b = xv[v];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const unsigned key = b[c] & 0x7FFFu;
+          if ((key >> 7) == d1) atomicAdd(&hist[H2 + rep * 128 + (key & 127u)], 1u);
+        }
+      }
+      __syncthreads();
+      find_digit(hist + H2, sm, 128, (unsigned)r.k - above1);
+      T = (d1 << 7) | sm.digit;
+      quota = (unsigned)r.k - above1 - sm.above;
+    }
+    unsigned gt = 0, eq = 0;
+    for (int v = v0; v < v1; ++v) {
+      const u16x8 b = xv[v];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        if (topk) {
+          const unsigned key = b[c] & 0x7FFFu;
+          gt += key > T;
+          eq += key == T;
+        } else {
+          gt += fabsf((float)__builtin_bit_cast(half_t, (unsigned short)b[c])) > r.t;
+        }
+      }
+    }
+    const unsigned pre = excl_scan(gt | (eq << 16), sm);
+    const unsigned tot = sm.total;
+    const int nidx = (int)((tot & 0xFFFFu) + min(tot >> 16, quota));
+    *nidx_total = nidx;
+    const int R = (nidx + S - 1) / S;
+    const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+    unsigned pos = (pre & 0xFFFFu) + min(pre >> 16, quota);
+    unsigned eq_seen = pre >> 16;
+    // only threads whose run overlaps the split's positions need the second look
+    const unsigned my_kept = gt + (min(eq_seen + eq, quota) - min(eq_seen, quota));
+    if ((int)(pos + my_kept) > r0 && (int)pos < r1) {
+      for (int v = v0; v < v1; ++v) {
+        const u16x8 b = xv[v];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const unsigned bits = b[c];
+          bool keep;
+          if (topk) {
+            const unsigned key = bits & 0x7FFFu;
+            keep = key > T;
+            if (key == T) {
+              keep = eq_seen < quota;
+              ++eq_seen;
+            }
+          } else {
+            keep = fabsf((float)__builtin_bit_cast(half_t, (unsigned short)bits)) > r.t;
+          }
+          if (keep) {
+            if ((int)pos >= r0 && (int)pos < r1) {
+              const int j = v * 8 + c;
+              list[pos - r0] = ((unsigned)j << 16) | bits;
+              if (store_idx && r.idx_out != nullptr) r.idx_out[pos] = j;
+            }
+            ++pos;
+          }
+        }
+      }
+    }
+    if (store_count && r.count_out != nullptr && tid == 0) *r.count_out = nidx;
+    __syncthreads();
+    return r1 - r0;
+  }
+};

@@ -104,7 +104,14 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(af_select_args a) {
   // ---- producer: bring x into LDS (and to x_out when it is computed here) --------------
   if (PRODUCER == AF_PRO_NONE) {
     const unsigned short* src = reinterpret_cast<const unsigned short*>(a.src);
-    for (int j = tid; j < n; j += SEL_THREADS) xs[j] = src[j];
+    for (int j0 = tid; j0 < n; j0 += 4 * SEL_THREADS) {  // four loads in flight per thread
+      unsigned short t[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) t[u] = (j0 + u * SEL_THREADS < n) ? src[j0 + u * SEL_THREADS] : 0;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (j0 + u * SEL_THREADS < n) xs[j0 + u * SEL_THREADS] = t[u];
+    }
   } else if (PRODUCER == AF_PRO_RMSNORM) {
     float ss = 0.f;
     for (int j = tid; j < n; j += SEL_THREADS) {
