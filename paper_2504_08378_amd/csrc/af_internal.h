@@ -149,4 +149,41 @@ __device__ __forceinline__ int af_ticket_take(int* t) {
 }
 #endif
 
+#ifdef __HIPCC__
+// ---- wave64 scans and sums on the DPP data path ------------------------------------------
+// Inclusive prefix sum over the 64 lanes of a wave: four row_shr steps scan each row of 16
+// lanes (lanes shifted in from outside the row read 0), row_bcast:15 adds a row's total to
+// the next row (rows 1 and 3), row_bcast:31 adds the total of rows 0-1 to rows 2-3.  These
+// are VALU operations; the shuffle intrinsics go through the LDS crossbar instead and cost
+// several hundred cycles for the same scan.
+__device__ __forceinline__ unsigned af_wave_incl_scan(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+  return v;
+}
+__device__ __forceinline__ float af_wave_incl_scan(float v) {
+#define AF_DPP_F(ctrl, rmask) \
+  __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xf, false))
+  v += AF_DPP_F(0x111, 0xf);
+  v += AF_DPP_F(0x112, 0xf);
+  v += AF_DPP_F(0x114, 0xf);
+  v += AF_DPP_F(0x118, 0xf);
+  v += AF_DPP_F(0x142, 0xa);
+  v += AF_DPP_F(0x143, 0xc);
+#undef AF_DPP_F
+  return v;
+}
+// Sum over the wave, returned to every lane (lane 63 of the scan holds it).
+__device__ __forceinline__ unsigned af_wave_sum(unsigned v) {
+  return (unsigned)__builtin_amdgcn_readlane((int)af_wave_incl_scan(v), 63);
+}
+__device__ __forceinline__ float af_wave_sum(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, af_wave_incl_scan(v)), 63));
+}
+#endif
+
 static inline size_t af_align(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }

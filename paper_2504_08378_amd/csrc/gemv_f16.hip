@@ -19,8 +19,6 @@
 #include "af_internal.h"
 #include "row_prologue.h"
 
-#define GEMV_THREADS 256
-#define GEMV_WAVES (GEMV_THREADS / AF_WAVE)
 #define GEMV_LIST 2048  // staged rows per pass: (index << 16 | fp16 bits of x)
 
 struct GemvParams {
@@ -41,19 +39,21 @@ __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v)
     reinterpret_cast<float*>(p.y)[col] = v;
 }
 
-template <int LX, int U>
-__global__ __launch_bounds__(GEMV_THREADS) void gemv_f16_kernel(GemvParams p) {
+template <int LX, int U, int NW>
+__global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
+  constexpr int GEMV_THREADS = NW * AF_WAVE;
+  constexpr int GEMV_WAVES = NW;
   constexpr int LY = AF_WAVE / LX;
   constexpr int TW = LX * 8;
   constexpr int STEP = GEMV_WAVES * LY;  // rows taken per workgroup iteration
+  constexpr int SCRATCH = RP_SCRATCH_WORDS > NW * TW ? RP_SCRATCH_WORDS : NW * TW;
   typedef RowPrologue<GEMV_THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];  // the operator input, when built here
-  __shared__ unsigned s_scratch[RP_SCRATCH_WORDS]; // histograms, later the wave sums
+  __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
   __shared__ unsigned s_list[GEMV_LIST];
   __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
   float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
-  static_assert(GEMV_WAVES * TW <= RP_SCRATCH_WORDS, "wave sums must fit the scratch area");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
@@ -168,18 +168,26 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_f16_kernel(GemvParams p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
 }
 
-// Tile width and split count for a shape.  AF_GEMV_LX / AF_GEMV_SPLIT / AF_GEMV_WGS in the
-// environment override the heuristic (used by tuning sweeps).
-static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int* s_out) {
+// Tile width, waves per workgroup and split count for a shape.  AF_GEMV_LX / AF_GEMV_NW /
+// AF_GEMV_SPLIT / AF_GEMV_WGS in the environment override the heuristic (tuning sweeps).
+static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, int* lx_out,
+                          int* nw_out, int* s_out) {
   // Measured on the 7B operators (cold matrices): 128-column tiles (256 B per row and
-  // workgroup) win up to ~16K columns, 256-column tiles beyond; narrow outputs want about one
-  // workgroup per CU (long row loops, few partials), wide ones about four.
+  // workgroup) win up to ~16K columns, 256-column tiles beyond.  A kernel that selects for
+  // itself repeats the selection in every workgroup, so it runs few, large workgroups
+  // (one per CU); a plain GEMV prefers several small ones per CU.
   int lx = out <= 16384 ? 16 : 32;
-  int target_wgs = out <= 4096 ? ctx->n_cu : ctx->n_cu * 4;
+  int nw = selects ? 16 : 4;
   if (const char* e = getenv("AF_GEMV_LX")) {
     int v = atoi(e);
     if (v == 16 || v == 32 || v == 64) lx = v;
   }
+  if (const char* e = getenv("AF_GEMV_NW")) {
+    int v = atoi(e);
+    if (v == 4 || v == 8 || v == 16) nw = v;
+  }
+  const int per_cu = 16 / nw;  // workgroups of nw waves that one CU holds at a time
+  int target_wgs = nw == 4 ? (out <= 4096 ? ctx->n_cu : ctx->n_cu * 4) : ctx->n_cu * per_cu;
   if (const char* e = getenv("AF_GEMV_WGS")) {
     int v = atoi(e);
     if (v > 0) target_wgs = v;
@@ -197,7 +205,29 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, int* lx_out, int
   if (S > 256) S = 256;
   if (S < 1) S = 1;
   *lx_out = lx;
+  *nw_out = nw;
   *s_out = S;
+}
+
+template <int LX, int NW>
+static void launch_one(dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
+  static bool attr_done = false;
+  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
+    attr_done = true;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+  }
+  hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
+}
+
+template <int LX>
+static void launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
+  if (nw == 16)
+    launch_one<LX, 16>(grid, lds, st, p);
+  else if (nw == 8)
+    launch_one<LX, 8>(grid, lds, st, p);
+  else
+    launch_one<LX, 4>(grid, lds, st, p);
 }
 
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
@@ -205,8 +235,8 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   // the largest index set this launch can meet (the count of a threshold set is only known
   // on the device)
   int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
-  int lx, S;
-  choose_config(ctx, a.out, max_rows, &lx, &S);
+  int lx, nw, S;
+  choose_config(ctx, a.out, max_rows, r.sel != AF_ROWS_GIVEN, &lx, &nw, &S);
   const int tw = lx * 8;
   const int tiles = (a.out + tw - 1) / tw;
   const int out_pad = tiles * tw;
@@ -231,23 +261,13 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.out_pad = out_pad;
   p.use_lds_x = (r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN) ? 1 : 0;
   const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
-  static bool attr_done = false;
-  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
-    attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<16, 8>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<32, 8>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<64, 8>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
-  }
-  dim3 grid(tiles, S), block(GEMV_THREADS);
+  dim3 grid(tiles, S);
   if (lx == 64)
-    hipLaunchKernelGGL((gemv_f16_kernel<64, 8>), grid, block, lds, ctx->stream, p);
+    launch_lx<64>(nw, grid, lds, ctx->stream, p);
   else if (lx == 32)
-    hipLaunchKernelGGL((gemv_f16_kernel<32, 8>), grid, block, lds, ctx->stream, p);
+    launch_lx<32>(nw, grid, lds, ctx->stream, p);
   else
-    hipLaunchKernelGGL((gemv_f16_kernel<16, 8>), grid, block, lds, ctx->stream, p);
+    launch_lx<16>(nw, grid, lds, ctx->stream, p);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }

@@ -58,8 +58,7 @@ struct RowPrologue {
           if (v0 + u * THREADS < nvec) xv[v0 + u * THREADS] = t[u];  // raw; normalised below
         }
       }
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, AF_WAVE);
+      ss = af_wave_sum(ss);
       if (lane == 0) sm.red[wave] = ss;
       __syncthreads();
       float tot = 0.f;
@@ -139,13 +138,9 @@ struct RowPrologue {
       const unsigned b0 = sm.merged[4 * tid], b1 = sm.merged[4 * tid + 1],
                      b2 = sm.merged[4 * tid + 2], b3 = sm.merged[4 * tid + 3];
       const unsigned mine = b0 + b1 + b2 + b3;
-      unsigned v = mine;
-#pragma unroll
-      for (int off = 1; off < AF_WAVE; off <<= 1) {
-        const unsigned o = __shfl_down(v, off, AF_WAVE);
-        if (tid + off < AF_WAVE) v += o;
-      }
-      unsigned above = v - mine;
+      const unsigned pre = af_wave_incl_scan(mine);                       // bins of lanes <= mine
+      const unsigned all = (unsigned)__builtin_amdgcn_readlane((int)pre, 63);
+      unsigned above = all - pre;                                         // bins of higher lanes
       const unsigned cnt[4] = {b0, b1, b2, b3};
 #pragma unroll
       for (int q = 3; q >= 0; --q) {
@@ -162,12 +157,7 @@ struct RowPrologue {
   // exclusive prefix over the workgroup in thread order; total left in sm.total
   static __device__ __forceinline__ unsigned excl_scan(unsigned v, Smem& sm) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned inc = v;
-#pragma unroll
-    for (int off = 1; off < AF_WAVE; off <<= 1) {
-      const unsigned o = __shfl_up(inc, off, AF_WAVE);
-      if (lane >= off) inc += o;
-    }
+    const unsigned inc = af_wave_incl_scan(v);
     if (lane == 63) sm.wave_tot[wave] = inc;
     __syncthreads();
     unsigned base = 0, tot = 0;
@@ -198,8 +188,25 @@ struct RowPrologue {
     const int v0 = min(tid * cv, nvec), v1 = min(v0 + cv, nvec);
     const u16x8* xv = reinterpret_cast<const u16x8*>(xs);
     const int rep = lane & (RP_HIST_COPIES - 1);
-    unsigned T = 0x8000u, quota = 0;
+    // Both selection rules become integer tests on the magnitude key:
+    //   kept outright  <=>  (int)key > T  and  key <= kmax
+    //   tie candidates <=>  key == T, kept while the quota lasts (top-k only)
+    // top-k: T from the radix select below, kmax = 0x7FFF.  threshold: |x| > t  <=>  key >
+    // bits(largest fp16 <= t) for t >= 0 (T = -1 passes everything for t < 0); kmax = 0x7C00
+    // keeps NaN out, quota = 0.
+    int T = 0x8000;
+    unsigned quota = 0, kmax = 0x7FFFu;
     const bool topk = r.sel == AF_SEL_TOPK;
+    if (!topk) {
+      kmax = 0x7C00u;
+      if (r.t < 0.f) {
+        T = -1;
+      } else {
+        typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+        const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(r.t, 0.f);  // toward zero = downward for t >= 0
+        T = (int)(__builtin_bit_cast(unsigned, h) & 0x7FFFu);
+      }
+    }
     if (topk && r.k > 0) {
       zero_hist(hist);
       __syncthreads();
@@ -222,7 +229,7 @@ struct RowPrologue {
       }
       __syncthreads();
       find_digit(hist + H2, sm, 128, (unsigned)r.k - above1);
-      T = (d1 << 7) | sm.digit;
+      T = (int)((d1 << 7) | sm.digit);
       quota = (unsigned)r.k - above1 - sm.above;
     }
     unsigned gt = 0, eq = 0;
@@ -230,13 +237,9 @@ struct RowPrologue {
       const u16x8 b = xv[v];
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
-        if (topk) {
-          const unsigned key = b[c] & 0x7FFFu;
-          gt += key > T;
-          eq += key == T;
-        } else {
-          gt += fabsf((float)__builtin_bit_cast(half_t, (unsigned short)b[c])) > r.t;
-        }
+        const unsigned key = b[c] & 0x7FFFu;
+        gt += ((int)key > T) & (key <= kmax);
+        eq += (int)key == T;
       }
     }
     const unsigned pre = excl_scan(gt | (eq << 16), sm);
@@ -250,30 +253,22 @@ struct RowPrologue {
     // only threads whose run overlaps the split's positions need the second look
     const unsigned my_kept = gt + (min(eq_seen + eq, quota) - min(eq_seen, quota));
     if ((int)(pos + my_kept) > r0 && (int)pos < r1) {
+      const bool to_mem = store_idx && r.idx_out != nullptr;
       for (int v = v0; v < v1; ++v) {
         const u16x8 b = xv[v];
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
           const unsigned bits = b[c];
-          bool keep;
-          if (topk) {
-            const unsigned key = bits & 0x7FFFu;
-            keep = key > T;
-            if (key == T) {
-              keep = eq_seen < quota;
-              ++eq_seen;
-            }
-          } else {
-            keep = fabsf((float)__builtin_bit_cast(half_t, (unsigned short)bits)) > r.t;
+          const unsigned key = bits & 0x7FFFu;
+          const bool is_eq = (int)key == T;
+          const bool keep = (((int)key > T) & (key <= kmax)) | (is_eq & (eq_seen < quota));
+          eq_seen += is_eq;
+          if (keep & ((int)pos >= r0) & ((int)pos < r1)) {
+            const int j = v * 8 + c;
+            list[pos - r0] = ((unsigned)j << 16) | bits;
+            if (to_mem) r.idx_out[pos] = j;
           }
-          if (keep) {
-            if ((int)pos >= r0 && (int)pos < r1) {
-              const int j = v * 8 + c;
-              list[pos - r0] = ((unsigned)j << 16) | bits;
-              if (store_idx && r.idx_out != nullptr) r.idx_out[pos] = j;
-            }
-            ++pos;
-          }
+          pos += keep;
         }
       }
     }

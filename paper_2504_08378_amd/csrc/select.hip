@@ -25,14 +25,7 @@ struct SelSmem {
   unsigned total;
 };
 
-__device__ __forceinline__ unsigned wave_incl_scan(unsigned v, int lane) {
-#pragma unroll
-  for (int off = 1; off < AF_WAVE; off <<= 1) {
-    unsigned o = __shfl_up(v, off, AF_WAVE);
-    if (lane >= off) v += o;
-  }
-  return v;
-}
+__device__ __forceinline__ unsigned wave_incl_scan(unsigned v, int) { return af_wave_incl_scan(v); }
 
 // Exclusive prefix of v over the block in thread order; total in sm.total.
 __device__ __forceinline__ unsigned block_excl_scan(unsigned v, SelSmem& sm) {
@@ -69,13 +62,8 @@ __device__ __forceinline__ void find_digit(SelSmem& sm, int nbins, unsigned want
     unsigned b0 = sm.merged[4 * tid], b1 = sm.merged[4 * tid + 1], b2 = sm.merged[4 * tid + 2],
              b3 = sm.merged[4 * tid + 3];
     unsigned mine = b0 + b1 + b2 + b3;
-    unsigned v = mine;
-#pragma unroll
-    for (int off = 1; off < AF_WAVE; off <<= 1) {
-      unsigned o = __shfl_down(v, off, AF_WAVE);
-      if (tid + off < AF_WAVE) v += o;
-    }
-    unsigned above = v - mine;  // count in bins of higher lanes
+    const unsigned pre = af_wave_incl_scan(mine);
+    unsigned above = (unsigned)__builtin_amdgcn_readlane((int)pre, 63) - pre;  // bins of higher lanes
     // walk my four bins from the top
     unsigned cnt[4] = {b0, b1, b2, b3};
 #pragma unroll
@@ -118,8 +106,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(af_select_args a) {
       float v = (float)a.src[j];
       ss += v * v;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, AF_WAVE);
+    ss = af_wave_sum(ss);
     if (lane == 0) sm.red[wave] = ss;
     __syncthreads();
     float tot = 0.f;
