@@ -27,37 +27,21 @@ struct AttnParams {
   half_t* out;         // [n_heads*HD]
   float* part;         // [n_heads][KS][HD+2]
   int* tickets;        // [n_heads]
-  int n_heads, n_kv, kv_len, kv_cap, pos;
-  float theta;
+  int n_heads, n_kv, kv_len, kv_cap;
+  float cs[64], sn[64];  // cos / sin of pos * theta^(-2i/HD), i < HD/2, formed in fp64 on the host
 };
-
-// Rotate the pair (a, b) = (v[i], v[i + HD/2]) by pos * theta^(-2i/HD).  The angle is formed in
-// fp64 and reduced to [-pi, pi] before the fp32 sincos, so large positions lose nothing.
-template <int HD>
-__device__ __forceinline__ void rope_pair(int i, int pos, float theta, float a, float b, float* ra,
-                                          float* rb) {
-  const double inv = exp2(-(2.0 * (double)i / (double)HD) * log2((double)theta));
-  double ang = (double)pos * inv;
-  const double two_pi = 6.283185307179586476925286766559;
-  ang -= two_pi * rint(ang / two_pi);
-  float sn, cs;
-  sincosf((float)ang, &sn, &cs);
-  *ra = a * cs - b * sn;
-  *rb = b * cs + a * sn;
-}
 
 template <int HD>
 __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) {
   constexpr int LPK = HD / 8;             // lanes per key (8 dims = 16 bytes each)
-  constexpr int KPW = AF_WAVE / LPK;      // keys per wave instruction
   constexpr int KPB = ATT_THREADS / LPK;  // keys per workgroup iteration
+  constexpr int NB = 4;                   // iterations whose loads are issued together
   __shared__ float s_q[HD];
   __shared__ float s_knew[HD];
   __shared__ float s_vnew[HD];
   __shared__ float s_sc[ATT_MAX_KEYS + 1];
   __shared__ float s_pv[KPB][HD];
   __shared__ float s_red[ATT_WAVES];
-  __shared__ float s_m, s_l;
   __shared__ int s_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -75,18 +59,32 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   const half_t* vn = p.qkv + (size_t)(p.n_heads + p.n_kv + kvh) * HD;
   half_t* Kc = p.k_cache + (size_t)kvh * p.kv_cap * HD;
   half_t* Vc = p.v_cache + (size_t)kvh * p.kv_cap * HD;
+  const int lk = tid % LPK, kq = tid / LPK;  // my slice of the head dim, my key slot
+  half8 zero8;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) zero8[c] = (half_t)0;
+
+  // the first NB key/value rows of this thread go out before anything else needs them
+  half8 kv[NB], vv[NB];
+#pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    const int i = kq + u * KPB;
+    const bool ok = i < cnt;
+    kv[u] = ok ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    vv[u] = ok ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+  }
 
   if (tid < HD / 2) {
-    float ra, rb;
-    rope_pair<HD>(tid, p.pos, p.theta, (float)q[tid], (float)q[tid + HD / 2], &ra, &rb);
+    const float a = (float)q[tid], b = (float)q[tid + HD / 2];
+    const float cs = p.cs[tid], sn = p.sn[tid];
     const float sc = 1.0f / sqrtf((float)HD);
-    s_q[tid] = ra * sc;
-    s_q[tid + HD / 2] = rb * sc;
+    s_q[tid] = (a * cs - b * sn) * sc;
+    s_q[tid + HD / 2] = (b * cs + a * sn) * sc;
   } else if (owns_new && tid >= 64 && tid < 64 + HD / 2) {
     const int i = tid - 64;
-    float ra, rb;
-    rope_pair<HD>(i, p.pos, p.theta, (float)kn[i], (float)kn[i + HD / 2], &ra, &rb);
-    const half_t ha = (half_t)ra, hb = (half_t)rb;  // the cache holds fp16
+    const float a = (float)kn[i], b = (float)kn[i + HD / 2];
+    const float cs = p.cs[i], sn = p.sn[i];
+    const half_t ha = (half_t)(a * cs - b * sn), hb = (half_t)(b * cs + a * sn);  // cache is fp16
     s_knew[i] = (float)ha;
     s_knew[i + HD / 2] = (float)hb;
     if (h % rep == 0) {
@@ -102,24 +100,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   __syncthreads();
 
   // ---- scores ------------------------------------------------------------------------
-  const int lk = tid % LPK, kq = tid / LPK;  // my slice of the head dim, my key slot
   float qr[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) qr[c] = s_q[lk * 8 + c];
-  for (int i = kq; i < cnt; i += KPB) {
-    half8 kv = *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8);
+  auto score = [&](const half8& k8, int i) {
     float d = 0.f;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) d += (float)kv[c] * qr[c];
+    for (int c = 0; c < 8; ++c) d += (float)k8[c] * qr[c];
 #pragma unroll
     for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off, AF_WAVE);
-    if (lk == 0) s_sc[i] = d;
+    if (lk == 0 && i < cnt) s_sc[i] = d;
+  };
+#pragma unroll
+  for (int u = 0; u < NB; ++u) score(kv[u], kq + u * KPB);
+  for (int i0 = kq + NB * KPB; i0 < cnt; i0 += NB * KPB) {  // long caches: further batches
+    half8 k2[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      k2[u] = i < cnt ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) score(k2[u], i0 + u * KPB);
   }
   if (owns_new && wave == 0) {
     float d = 0.f;
     for (int c = lane; c < HD; c += AF_WAVE) d += s_q[c] * s_knew[c];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, AF_WAVE);
+    d = af_wave_sum(d);
     if (lane == 0) s_sc[cnt] = d;
   }
   __syncthreads();
@@ -141,8 +148,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
     s_sc[i] = e;
     l += e;
   }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, AF_WAVE);
+  l = af_wave_sum(l);
   if (lane == 0) s_red[wave] = l;
   __syncthreads();
   l = 0.f;
@@ -153,11 +159,27 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   float acc[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
-  for (int i = kq; i < cnt; i += KPB) {
-    half8 vv = *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8);
-    const float pw = s_sc[i];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] += pw * (float)vv[c];
+  for (int u = 0; u < NB; ++u) {
+    const int i = kq + u * KPB;
+    const float pw = i < cnt ? s_sc[i] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] += pw * (float)vv[u][c];
+  }
+  for (int i0 = kq + NB * KPB; i0 < cnt; i0 += NB * KPB) {
+    half8 v2[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      v2[u] = i < cnt ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      const float pw = i < cnt ? s_sc[i] : 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] += pw * (float)v2[u][c];
+    }
   }
 #pragma unroll
   for (int c = 0; c < 8; ++c) s_pv[kq][lk * 8 + c] = acc[c];
@@ -187,20 +209,37 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   }
   __syncthreads();
   if (!s_last) return;
-  // combine the splits in order
+  // combine the splits in split order; loads go out eight splits at a time
   const float* base = p.part + (size_t)h * KS * (HD + 2);
-  float M = -INFINITY;
-  for (int q2 = 0; q2 < KS; ++q2)
-    M = fmaxf(M, af_load_agent(base + (size_t)q2 * (HD + 2)));
   if (tid < HD) {
+    float M = -INFINITY;
+    for (int q0 = 0; q0 < KS; q0 += 8) {
+      float ms[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        ms[u] = q0 + u < KS ? af_load_agent(base + (size_t)(q0 + u) * (HD + 2)) : -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) M = fmaxf(M, ms[u]);
+    }
     float L = 0.f, v = 0.f;
-    for (int q2 = 0; q2 < KS; ++q2) {
-      const float* pp = base + (size_t)q2 * (HD + 2);
-      const float ms = af_load_agent(pp);
-      if (ms == -INFINITY) continue;  // an empty split
-      const float wgt = expf(ms - M);
-      L += wgt * af_load_agent(pp + 1);
-      v += wgt * af_load_agent(pp + 2 + tid);
+    for (int q0 = 0; q0 < KS; q0 += 8) {
+      float ms[8], ls[8], av[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool ok = q0 + u < KS;
+        const float* pp = base + (size_t)(q0 + u) * (HD + 2);
+        ms[u] = ok ? af_load_agent(pp) : -INFINITY;
+        ls[u] = ok ? af_load_agent(pp + 1) : 0.f;
+        av[u] = ok ? af_load_agent(pp + 2 + tid) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (ms[u] != -INFINITY) {  // an empty split has nothing to add
+          const float wgt = expf(ms[u] - M);
+          L += wgt * ls[u];
+          v += wgt * av[u];
+        }
+      }
     }
     p.out[(size_t)h * HD + tid] = (half_t)(v / L);
   }
@@ -225,8 +264,11 @@ static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* 
   p.n_kv = cfg->n_kv_heads;
   p.kv_len = kv_len;
   p.kv_cap = kv_cap;
-  p.pos = pos;
-  p.theta = cfg->rope_theta;
+  for (int i = 0; i < cfg->head_dim / 2; ++i) {
+    const double ang = (double)pos * pow((double)cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
+    p.cs[i] = (float)cos(ang);
+    p.sn[i] = (float)sin(ang);
+  }
   dim3 grid(cfg->n_heads, KS);
   if (cfg->head_dim == 128)
     hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(ATT_THREADS), 0, ctx->stream, p);
