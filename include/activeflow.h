@@ -115,6 +115,22 @@ int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, i
                       int ld, const void* x_f16, const int32_t* idx, int nidx_host,
                       const int32_t* nidx_dev, void* y, int y_kind, const void* residual_f16);
 
+/* ---- fused front end: operations T and C of Section 4 in one launch --------------------
+ * The GEMV kernel builds its own input vector and selects on it, so no activation or index
+ * list has to travel through memory between a producer, a selection and the GEMV:
+ *   producer AF_PRO_NONE    x = src                      (src fp16 [in])
+ *            AF_PRO_RMSNORM x = fp16(src * rsqrt(mean(src^2) + eps) * gain)   (src, gain [in])
+ *            AF_PRO_SILUMUL x = fp16(silu(src[j]) * src[in + j])              (src [2*in])
+ *   sel_mode AF_SEL_TOPK (k) | AF_SEL_THRESHOLD (t) | AF_SEL_DENSE (all channels)
+ *   y = Wt[idx][:]^T x[idx] (+ residual), idx = select(x) as af_select_topk/_threshold define it.
+ * Optional outputs (NULL to skip): x_out fp16 [in] the produced vector; idx_out int32 [in]
+ * and count_out int32 [1] the index set.  in % 8 == 0; other rules as af_sparse_gemv_f16. */
+enum { AF_PRO_NONE = 0, AF_PRO_RMSNORM = 1, AF_PRO_SILUMUL = 2 };
+int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, int producer,
+                       const void* src_f16, const void* gain_f16, float eps, int sel_mode, int k,
+                       float t, void* x_out, int32_t* idx_out, int32_t* count_out, void* y,
+                       int y_kind, const void* residual_f16);
+
 /* ---- small-batch union GEMV (extension of operation C to B tokens) ----------------------
  * Each of the B <= AF_MAX_BATCH tokens has its own index set idx_b[b][0..k); the kernel
  * reads every row of the union once and applies each token's mask:

@@ -18,12 +18,13 @@ LIB_PATH = os.path.join(_PKG, "libactiveflow.so")
 AF_F16, AF_F32 = 0, 1
 AF_W_F16, AF_W_Q4G32 = 0, 1
 AF_SEL_TOPK, AF_SEL_THRESHOLD, AF_SEL_DENSE = 0, 1, 2
+AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
 
 EXPORTS = [
     "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
     "af_set_workspace", "af_select_topk", "af_select_threshold", "af_pack_inmajor_f16",
-    "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_sparse_gemv_union_f16",
+    "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_select_gemv_f16", "af_sparse_gemv_union_f16",
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
     "af_graph_launch", "af_graph_destroy",
 ]
@@ -83,6 +84,7 @@ def lib() -> C.CDLL:
         "af_pack_q4_g32": (i, [vp, vp, i, i, vp, vp, i, i]),
         "af_sparse_gemv_f16": (i, [vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
         "af_sparse_gemv_q4": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_select_gemv_f16": (i, [vp, vp, i, i, i, i, vp, vp, f, i, i, f, vp, vp, vp, vp, i, vp]),
         "af_sparse_gemv_union_f16": (i, [vp, vp, i, i, i, vp, i, vp, i, vp, vp, vp, i]),
         "af_decode_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, vp,
                                 i, i, i, C.POINTER(SelectCfg), C.POINTER(IdxSets)]),
@@ -237,6 +239,23 @@ class Context:
             n_in, out, ld, _ptr(x, torch.float16, "x"), _ptr(idx, torch.int32, "idx"),
             int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"), _ptr(y, None, "y"), y_kind,
             _ptr(residual, torch.float16, "residual")), "af_sparse_gemv_q4")
+        return y
+
+    def select_gemv_f16(self, Wt, src, producer=AF_PRO_NONE, gain=None, eps=1e-5,
+                        sel_mode=AF_SEL_TOPK, k=0, t=0.0, x_out=None, idx_out=None, count_out=None,
+                        y=None, y_kind=AF_F16, residual=None, out=None):
+        n_in, ld = Wt.shape
+        out = ld if out is None else out
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        _check(lib().af_select_gemv_f16(
+            self._h, _ptr(Wt, torch.float16, "Wt"), n_in, out, ld, producer,
+            _ptr(src, torch.float16, "src"), _ptr(gain, torch.float16, "gain"), float(eps),
+            sel_mode, int(k), float(t), _ptr(x_out, torch.float16, "x_out"),
+            _ptr(idx_out, torch.int32, "idx_out"), _ptr(count_out, torch.int32, "count_out"),
+            _ptr(y, None, "y"), y_kind, _ptr(residual, torch.float16, "residual")),
+            "af_select_gemv_f16")
         return y
 
     def sparse_gemv_union_f16(self, Wt, X, idx_b, y_kind=AF_F16, out=None):

@@ -54,7 +54,6 @@ static inline int af_hip(hipError_t e) { return e == hipSuccess ? AF_OK : AF_EHI
 //   AF_PRO_NONE    x = src
 //   AF_PRO_RMSNORM x = fp16(src * rsqrt(mean(src^2) + eps) * gain); x is also stored to x_out
 //   AF_PRO_SILUMUL x = fp16(silu(src[j]) * src[n + j]);             x is also stored to x_out
-enum { AF_PRO_NONE = 0, AF_PRO_RMSNORM = 1, AF_PRO_SILUMUL = 2 };
 struct af_select_args {
   const half_t* src;
   const half_t* gain;  // rmsnorm only

@@ -304,3 +304,49 @@ extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
   a.residual = (const half_t*)residual_f16;
   return af_launch_gemv_f16(ctx, a);
 }
+
+extern "C" int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, int producer,
+                                  const void* src_f16, const void* gain_f16, float eps,
+                                  int sel_mode, int k, float t, void* x_out, int32_t* idx_out,
+                                  int32_t* count_out, void* y, int y_kind,
+                                  const void* residual_f16) {
+  if (!ctx || !Wt || !src_f16 || !y) return AF_ENULL;
+  if (producer != AF_PRO_NONE && producer != AF_PRO_RMSNORM && producer != AF_PRO_SILUMUL)
+    return AF_EINVAL;
+  if (producer == AF_PRO_RMSNORM && !gain_f16) return AF_ENULL;
+  if (in <= 0 || out <= 0 || in > AF_MAX_N) return AF_EINVAL;
+  if (in % 8 || out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
+  if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
+  if (sel_mode != AF_SEL_TOPK && sel_mode != AF_SEL_THRESHOLD && sel_mode != AF_SEL_DENSE)
+    return AF_EINVAL;
+  if (sel_mode == AF_SEL_TOPK && (k < 0 || k > in)) return AF_EINVAL;
+  if (sel_mode == AF_SEL_THRESHOLD && t != t) return AF_EINVAL;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  if (in > ctx->max_in || out > ctx->max_out) return AF_EWORKSPACE;
+  af_gemv_args a{};
+  a.W = Wt;
+  a.in = in;
+  a.out = out;
+  a.ld = ld;
+  a.rows.pro = producer;
+  a.rows.src = (const half_t*)src_f16;
+  a.rows.gain = (const half_t*)gain_f16;
+  a.rows.eps = eps;
+  a.rows.x_out = (half_t*)x_out;
+  a.rows.n = in;
+  if (sel_mode == AF_SEL_DENSE) {
+    a.rows.sel = AF_ROWS_GIVEN;
+    a.rows.idx = nullptr;
+    a.rows.nidx_host = in;
+  } else {
+    a.rows.sel = sel_mode;
+    a.rows.k = k;
+    a.rows.t = t;
+    a.rows.idx_out = idx_out;
+    a.rows.count_out = count_out;
+  }
+  a.y = y;
+  a.y_kind = y_kind;
+  a.residual = (const half_t*)residual_f16;
+  return af_launch_gemv_f16(ctx, a);
+}

@@ -1,0 +1,119 @@
+"""GPU parity: af_select_gemv_f16 (producer + selection + gathered GEMV in one launch)
+against the oracle's separate steps.  The selection input of each case is computed by the
+oracle's own arithmetic on the same fp16 bits, so index sets are compared bit-for-bit where
+the producer is the identity; behind a norm / SwiGLU producer the GPU's own x is used to
+check the set from the definition and the oracle's set may differ only at the k-th magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import activeflow_oracle as O
+from paper_2504_08378_amd import binding as B
+from gpu_util import ctx, to_dev, to_host  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def _wx(out, n, seed):
+    W = S.weight_matrix(seed, out, n, "fused", out, n)
+    x = S.activation(seed, S.channel_scales(seed, n, "fused"), "fused", 0)
+    return W, x
+
+
+def _run(ctx, Wt, src, n, **kw):
+    xo = torch.zeros(n, dtype=torch.float16, device="cuda")
+    io = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    co = torch.zeros(1, dtype=torch.int32, device="cuda")
+    y = ctx.select_gemv_f16(Wt, src, x_out=xo, idx_out=io, count_out=co, **kw)
+    ctx.synchronize()
+    c = int(to_host(co)[0])
+    return to_host(y), to_host(xo), to_host(io)[:c], c
+
+
+@pytest.mark.parametrize("out,n,k", [(136, 64, 32), (520, 1000, 377), (4096, 4096, 2048),
+                                     (1032, 11008, 5504), (2056, 5120, 1536), (264, 28672, 14336)])
+def test_identity_producer_topk_is_bit_exact(ctx, out, n, k):
+    W, x = _wx(out, n, out + n)
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    y, _, idx, c = _run(ctx, Wt, to_dev(x), n, sel_mode=B.AF_SEL_TOPK, k=k, y_kind=B.AF_F32)
+    ref_idx = O.select_topk(x, k)
+    assert c == k and np.array_equal(idx, ref_idx)
+    assert O.rel_err(y, O.sparse_gemv(W, x, ref_idx)) <= 1e-4
+
+
+def test_threshold_dense_and_empty(ctx):
+    W, x = _wx(520, 2048, 5)
+    Wt = ctx.pack_inmajor_f16(to_dev(W)); xd = to_dev(x)
+    mags = np.sort(np.abs(x.astype(np.float64)))
+    for t in (-1.0, 0.0, float(mags[1024]), 0.37, 3.0, 1e9, float("inf")):
+        y, _, idx, c = _run(ctx, Wt, xd, 2048, sel_mode=B.AF_SEL_THRESHOLD, t=t, y_kind=B.AF_F32)
+        ref_idx = O.select_threshold(x, t)
+        assert c == len(ref_idx) and np.array_equal(idx, ref_idx), t
+        assert O.rel_err(y, O.sparse_gemv(W, x, ref_idx)) <= 1e-4, t
+    y = ctx.select_gemv_f16(Wt, xd, sel_mode=B.AF_SEL_DENSE, y_kind=B.AF_F32)
+    ctx.synchronize()
+    assert O.rel_err(to_host(y), O.sparse_gemv(W, x, np.arange(2048))) <= 1e-4
+    res = S.activation(5, S.channel_scales(5, 520, "r"), "r", 0)
+    y, _, idx, c = _run(ctx, Wt, xd, 2048, sel_mode=B.AF_SEL_TOPK, k=0, residual=to_dev(res))
+    assert c == 0 and np.array_equal(y, res)
+    # special values: NaN ranks highest for top-k and never passes a threshold
+    z = x.copy(); z[7] = np.nan; z[9] = np.inf; z[11] = -np.inf
+    _, _, idx, c = _run(ctx, Wt, to_dev(z), 2048, sel_mode=B.AF_SEL_TOPK, k=3)
+    assert idx.tolist() == [7, 9, 11]
+    _, _, idx, c = _run(ctx, Wt, to_dev(z), 2048, sel_mode=B.AF_SEL_THRESHOLD, t=1e4)
+    assert idx.tolist() == O.select_threshold(z, 1e4).tolist() == [9, 11]
+
+
+def _topk_property(x16, idx, k):
+    key = (np.asarray(x16).view(np.uint16) & 0x7FFF).astype(np.int64)
+    assert len(idx) == k and np.all(np.diff(idx) > 0)
+    sel = np.zeros(len(key), bool); sel[idx] = True
+    lo, hi = key[sel].min(), key[~sel].max()
+    assert lo >= hi
+    if lo == hi:
+        assert np.nonzero(sel & (key == lo))[0].max() < np.nonzero(~sel & (key == lo))[0].min()
+
+
+@pytest.mark.parametrize("n,out", [(256, 264), (4096, 12288), (5120, 1032)])
+def test_rmsnorm_producer(ctx, n, out):
+    W, h = _wx(out, n, n + 1)
+    g = S.norm_gain(3, n, "fused")
+    x_ref = O.round_f16(O.rmsnorm(h, g, 1e-5))
+    k = n // 2
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    y, x_gpu, idx, c = _run(ctx, Wt, to_dev(h), n, producer=B.AF_PRO_RMSNORM, gain=to_dev(g),
+                            eps=1e-5, sel_mode=B.AF_SEL_TOPK, k=k, y_kind=B.AF_F32)
+    assert O.rel_err(x_gpu, x_ref) <= TOL
+    _topk_property(x_gpu, idx, k)
+    ref_idx = O.select_topk(x_ref, k)
+    if np.array_equal(x_gpu.view(np.uint16), x_ref.view(np.uint16)):
+        assert np.array_equal(idx, ref_idx)
+    # the GEMV itself, judged on the GPU's own x and set
+    assert O.rel_err(y, O.sparse_gemv(W, x_gpu, idx)) <= 1e-4
+
+
+def test_silumul_producer(ctx):
+    n, out = 11008, 520
+    W, _ = _wx(out, n, 77)
+    sc = S.channel_scales(77, 2 * n, "gu")
+    gu = (S.activation(77, sc, "gu", 0).astype(np.float32) * 0.3).astype(np.float16)
+    x_ref = O.round_f16(O.silu(gu[:n]) * gu[n:].astype(np.float64))
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    k = O.keep_count(n, 50)
+    y, x_gpu, idx, c = _run(ctx, Wt, to_dev(gu), n, producer=B.AF_PRO_SILUMUL,
+                            sel_mode=B.AF_SEL_TOPK, k=k, y_kind=B.AF_F32)
+    assert O.rel_err(x_gpu, x_ref) <= TOL
+    _topk_property(x_gpu, idx, k)
+    assert O.rel_err(y, O.sparse_gemv(W, x_gpu, idx)) <= 1e-4
+
+
+def test_argument_errors(ctx):
+    W, x = _wx(64, 64, 1)
+    Wt = ctx.pack_inmajor_f16(to_dev(W)); xd = to_dev(x)
+    for kw, code in ((dict(producer=9), -1), (dict(sel_mode=5), -1), (dict(k=65), -1),
+                     (dict(producer=B.AF_PRO_RMSNORM), -2), (dict(sel_mode=B.AF_SEL_THRESHOLD, t=float("nan")), -1)):
+        with pytest.raises(B.AfError) as e:
+            ctx.select_gemv_f16(Wt, xd, **kw)
+        assert e.value.status == code, kw
