@@ -15,22 +15,19 @@
 // fp16 subtract of 1032 leaves the exact integers q = n - 8.  Nibbles sitting four bits higher
 // come out as 16*q and are multiplied with x/16 instead.  Accumulation is fp32.
 #include "af_internal.h"
+#include "row_prologue.h"
 
-#define Q4_THREADS 256
-#define Q4_WAVES (Q4_THREADS / AF_WAVE)
-#define Q4_CHUNK 1024
+#define Q4_LIST 2048  // staged rows per pass: (index << 16 | fp16 bits of x)
 
 struct Q4Params {
   const unsigned char* packed;
   const half_t* scales;
-  const half_t* x;
-  const int32_t* idx;
-  const int32_t* nidx_dev;
+  af_row_src rows;
   float* partials;
   int* tickets;
   void* y;
   const half_t* residual;
-  int out, ld, nidx_host, y_kind, out_pad;
+  int out, ld, y_kind, out_pad, use_lds_x;
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
@@ -62,15 +59,20 @@ __device__ __forceinline__ void q4_fma8(float* acc, unsigned w, float x, float x
   acc[7] += (float)d[1] * x16;
 }
 
-template <int LX, int U, bool HAS_IDX>
-__global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
+template <int LX, int U, int NW>
+__global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
+  constexpr int THREADS = NW * AF_WAVE;
   constexpr int LY = AF_WAVE / LX;
   constexpr int TW = LX * 8;
-  constexpr int NSLOT = Q4_WAVES * LY;  // row slices per workgroup
-  __shared__ int s_idx[Q4_CHUNK];
-  __shared__ float s_x[Q4_CHUNK];
-  __shared__ float s_red[Q4_WAVES][TW];
+  constexpr int NSLOT = NW * LY;  // row slices per workgroup
+  constexpr int SCRATCH = RP_SCRATCH_WORDS > NW * TW ? RP_SCRATCH_WORDS : NW * TW;
+  typedef RowPrologue<THREADS> RP;
+  extern __shared__ __align__(16) unsigned short xs[];
+  __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
+  __shared__ unsigned s_list[Q4_LIST];
+  __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
+  float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
@@ -78,11 +80,9 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
   const int col_ld = col < p.out ? col : 0;
   const int S = gridDim.y, s = blockIdx.y;
   const int slot = wave * LY + ly;
+  const af_row_src& r = p.rows;
 
-  int nidx = p.nidx_host;
-  if (p.nidx_dev) nidx = min(*p.nidx_dev, nidx);
-  const int R = (nidx + S - 1) / S;
-  const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+  if (p.use_lds_x) RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x);
 
   float yacc[8], acc[8];
 #pragma unroll
@@ -94,8 +94,8 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
   const size_t row_bytes = (size_t)(p.ld / 2);
   const unsigned char* wcol = p.packed + col_ld / 2;
 
-  auto consume = [&](int j, unsigned w, float xv) {
-    const int g = j >> 5;
+  auto consume = [&](unsigned e, unsigned w) {
+    const int g = (int)(e >> 21);  // (index >> 5)
     if (g != cur_g) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
@@ -105,42 +105,58 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
       cur_g = g;
       sc = *reinterpret_cast<const half8*>(p.scales + (size_t)g * p.ld + col_ld);
     }
+    const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu));
     q4_fma8(acc, w, xv, xv * 0.0625f);
   };
-
-  for (int base = r0; base < r1; base += Q4_CHUNK) {
-    const int cnt = min(Q4_CHUNK, r1 - base);
-    __syncthreads();
-    for (int i = tid; i < cnt; i += Q4_THREADS) {
-      int j = HAS_IDX ? p.idx[base + i] : base + i;
-      s_idx[i] = j;
-      s_x[i] = (float)p.x[j];
-    }
-    __syncthreads();
+  // One pass over `cnt` staged rows: every (wave, lane group) slot takes a contiguous slice,
+  // so it crosses few group boundaries.
+  auto stream = [&](int cnt) {
     const int per = (cnt + NSLOT - 1) / NSLOT;
     int i = min(slot * per, cnt);
     const int iend = min(i + per, cnt);
     for (; i + U <= iend; i += U) {
-      unsigned w[U];
-      float xv[U];
-      int jj[U];
+      unsigned w[U], e[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        jj[u] = s_idx[i + u];
-        xv[u] = s_x[i + u];
-        w[u] = *reinterpret_cast<const unsigned*>(wcol + (size_t)jj[u] * row_bytes);
+        e[u] = s_list[i + u];
+        w[u] = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes);
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) consume(jj[u], w[u], xv[u]);
+      for (int u = 0; u < U; ++u) consume(e[u], w[u]);
     }
     for (; i < iend; ++i) {
-      const int j = s_idx[i];
-      unsigned w = *reinterpret_cast<const unsigned*>(wcol + (size_t)j * row_bytes);
-      consume(j, w, s_x[i]);
+      const unsigned e = s_list[i];
+      const unsigned w = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e >> 16) * row_bytes);
+      consume(e, w);
+    }
+  };
+
+  if (r.sel != AF_ROWS_GIVEN) {
+    int nidx_total;
+    const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
+                                     blockIdx.x == 0 && s == 0, &nidx_total);
+    stream(cnt);
+  } else {
+    int nidx = r.nidx_host;
+    if (r.nidx_dev) nidx = min(*r.nidx_dev, nidx);
+    const int R = (nidx + S - 1) / S;
+    const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
+    const unsigned short* xg = reinterpret_cast<const unsigned short*>(r.src);
+    for (int base = r0; base < r1; base += Q4_LIST) {
+      const int cnt = min(Q4_LIST, r1 - base);
+      __syncthreads();
+      for (int i = tid; i < cnt; i += THREADS) {
+        const int j = r.idx ? r.idx[base + i] : base + i;
+        const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
+        s_list[i] = ((unsigned)j << 16) | bits;
+      }
+      __syncthreads();
+      stream(cnt);
     }
   }
 #pragma unroll
   for (int c = 0; c < 8; ++c) yacc[c] += (float)sc[c] * acc[c];
+  __syncthreads();  // s_scratch changes its role: histograms -> wave sums
 
 #pragma unroll
   for (int off = LX; off < AF_WAVE; off <<= 1)
@@ -154,21 +170,21 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
 
   const int tile0 = blockIdx.x * TW;
   if (S == 1) {
-    for (int c = tid; c < TW; c += Q4_THREADS) {
+    for (int c = tid; c < TW; c += THREADS) {
       if (tile0 + c < p.out) {
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < Q4_WAVES; ++w) v += s_red[w][c];
+        for (int w = 0; w < NW; ++w) v += s_red[w][c];
         q4_store_out(p, tile0 + c, v);
       }
     }
     return;
   }
   float* mine = p.partials + (size_t)s * p.out_pad;
-  for (int c = tid; c < TW; c += Q4_THREADS) {
+  for (int c = tid; c < TW; c += THREADS) {
     float v = 0.f;
 #pragma unroll
-    for (int w = 0; w < Q4_WAVES; ++w) v += s_red[w][c];
+    for (int w = 0; w < NW; ++w) v += s_red[w][c];
     af_store_agent(mine + tile0 + c, v);
   }
   af_stores_done();
@@ -179,7 +195,7 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
   }
   __syncthreads();
   if (!s_last) return;
-  for (int c = tid; c < TW; c += Q4_THREADS) {
+  for (int c = tid; c < TW; c += THREADS) {
     if (tile0 + c < p.out) {
       q4_store_out(p, tile0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
     }
@@ -187,59 +203,82 @@ __global__ __launch_bounds__(Q4_THREADS) void gemv_q4_kernel(Q4Params p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
-template <int LX, int U>
-static void launch_q4(bool has_idx, dim3 grid, hipStream_t st, const Q4Params& p) {
-  if (has_idx)
-    hipLaunchKernelGGL((gemv_q4_kernel<LX, U, true>), grid, dim3(Q4_THREADS), 0, st, p);
+template <int LX, int NW>
+static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
+  static bool attr_done = false;
+  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
+    attr_done = true;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+  }
+  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
+}
+
+template <int LX>
+static void q4_launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
+  if (nw == 16)
+    q4_launch_one<LX, 16>(grid, lds, st, p);
   else
-    hipLaunchKernelGGL((gemv_q4_kernel<LX, U, false>), grid, dim3(Q4_THREADS), 0, st, p);
+    q4_launch_one<LX, 4>(grid, lds, st, p);
 }
 
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
+  const af_row_src& r = a.rows;
+  const bool selects = r.sel != AF_ROWS_GIVEN;
+  const int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
+  // a lane covers 8 columns = 4 bytes of a packed row; tiles of 8*LX columns
   int lx = a.out <= 4096 ? 16 : (a.out <= 16384 ? 32 : 64);
+  int nw = selects ? 16 : 4;
   if (const char* e = getenv("AF_Q4_LX")) {
     int v = atoi(e);
     if (v == 16 || v == 32 || v == 64) lx = v;
+  }
+  if (const char* e = getenv("AF_Q4_NW")) {
+    int v = atoi(e);
+    if (v == 4 || v == 16) nw = v;
   }
   const int tw = lx * 8;
   const int tiles = (a.out + tw - 1) / tw;
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
-  int target = ctx->n_cu * 8;
+  int target = nw == 16 ? ctx->n_cu : ctx->n_cu * 4;
   if (const char* e = getenv("AF_Q4_WGS")) {
     int v = atoi(e);
     if (v > 0) target = v;
   }
-  int S = (target + tiles - 1) / tiles;
-  if (a.rows.pro != AF_PRO_NONE || a.rows.sel != AF_ROWS_GIVEN) return AF_EINVAL;  // no fused front end yet
-  int max_s = (a.rows.nidx_host + 63) / 64;
+  int S = target / tiles;
+  int max_s = (max_rows + 63) / 64;
   if (max_s < 1) max_s = 1;
   if (S > max_s) S = max_s;
   if (S > 256) S = 256;
+  if (S < 1) S = 1;
+  if (selects) {
+    const int need = (max_rows + Q4_LIST - 1) / Q4_LIST;
+    if (S < need) S = need;
+  }
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
+  if (selects && (size_t)S * Q4_LIST < (size_t)max_rows) return AF_EWORKSPACE;
   Q4Params p;
   p.packed = (const unsigned char*)a.W;
   p.scales = a.scales;
-  p.x = a.rows.src;
-  p.idx = a.rows.idx;
-  p.nidx_dev = a.rows.nidx_dev;
+  p.rows = r;
   p.partials = (float*)(ctx->ws + ctx->lay.partials);
   p.tickets = (int*)(ctx->ws + ctx->lay.tickets);
   p.y = a.y;
   p.residual = a.residual;
   p.out = a.out;
   p.ld = a.ld;
-  p.nidx_host = a.rows.nidx_host;
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
+  p.use_lds_x = (r.pro != AF_PRO_NONE || selects) ? 1 : 0;
+  const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
   dim3 grid(tiles, S);
-  const bool has_idx = a.rows.idx != nullptr;
   if (lx == 64)
-    launch_q4<64, 8>(has_idx, grid, ctx->stream, p);
+    q4_launch_lx<64>(nw, grid, lds, ctx->stream, p);
   else if (lx == 32)
-    launch_q4<32, 8>(has_idx, grid, ctx->stream, p);
+    q4_launch_lx<32>(nw, grid, lds, ctx->stream, p);
   else
-    launch_q4<16, 8>(has_idx, grid, ctx->stream, p);
+    q4_launch_lx<16>(nw, grid, lds, ctx->stream, p);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }

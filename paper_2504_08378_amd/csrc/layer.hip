@@ -3,15 +3,15 @@
 // linear operator and the gathered GEMV (operation C) behind it; Section 3's reuse of a
 // group leader's index sets is a bit mask over the four selection points.
 //
-// Launch sequence of one layer (all on the context's stream, no host synchronisation); with
-// fp16 weights the norm / SwiGLU producers and the selections run inside the GEMV kernels'
+// Launch sequence of one layer (all on the context's stream, no host synchronisation); the
+// norm / SwiGLU producers and the selections run inside the GEMV kernels'
 // front end, so a layer is five launches:
 //   1 gemv  Wqkv     on rmsnorm(hidden), selecting        -> x_qkv, idx0, qkv
 //   2 rope + kv append + attention                        -> attn
 //   3 gemv  Wo       on attn, selecting, + hidden         -> idx1, h_mid
 //   4 gemv  Wgateup  on rmsnorm(h_mid), selecting         -> x_gateup, idx2, gateup
 //   5 gemv  Wdown    on silu(gate)*up, selecting, + h_mid -> x_down, idx3, hidden_out
-// (4-bit weights still use the separate selection kernels of select.hip before each GEMV.)
+// (the same holds for 4-bit weights: gemv_q4.hip shares the front end).
 #include <math.h>
 
 #include "af_internal.h"
@@ -341,25 +341,6 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
     }
   }
 
-  // Separate selection kernel (used where the GEMV has no fused front end: 4-bit weights).
-  auto select_at = [&](int p, int producer, const half_t* src_v, const half_t* gain,
-                       half_t* x_out) -> int {
-    af_select_args a{};
-    a.src = src_v;
-    a.gain = gain;
-    a.x_out = x_out;
-    a.n = widths[p];
-    a.eps = cfg->rms_eps;
-    const bool reused = (reuse >> p) & 1u;
-    a.mode = reused ? AF_SEL_DENSE : sel->mode;  // a reused point only runs the producer
-    a.k = sel->k[p];
-    a.t = sel->t[p];
-    a.idx = own->idx[p];
-    a.count = own->count[p];
-    if (a.mode == AF_SEL_TOPK && a.k == 0) a.mode = AF_SEL_DENSE;         // empty set
-    if (producer == AF_PRO_NONE && a.mode == AF_SEL_DENSE) return AF_OK;  // nothing to do
-    return af_launch_select(ctx, producer, a);
-  };
   // GEMV at selection point p.  fused: the kernel builds x from `src_v` (producer) and selects
   // for itself; otherwise x is ready in `x` and the rows come from pt[p].
   auto gemv = [&](int p, const void* W, const void* Sc, int in, int out, int producer,
@@ -379,17 +360,6 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
     r.eps = cfg->rms_eps;
     const bool reused = (reuse >> p) & 1u;
     const bool selects = !reused && sel->mode != AF_SEL_DENSE;
-    if (q4) {
-      int rc2 = select_at(p, producer, src_v, gain, x);
-      if (rc2) return rc2;
-      r.pro = AF_PRO_NONE;
-      r.src = producer == AF_PRO_NONE ? src_v : x;
-      r.sel = AF_ROWS_GIVEN;
-      r.idx = pt[p].idx;
-      r.nidx_host = pt[p].nidx_host;
-      r.nidx_dev = pt[p].nidx_dev;
-      return af_launch_gemv_q4(ctx, a);
-    }
     r.pro = producer;
     r.src = src_v;
     r.gain = gain;
@@ -406,7 +376,7 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
       r.nidx_host = pt[p].nidx_host;
       r.nidx_dev = pt[p].nidx_dev;
     }
-    return af_launch_gemv_f16(ctx, a);
+    return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a);
   };
 
   if ((rc = gemv(0, w->Wqkv, w->Sqkv, d, qkv_out, AF_PRO_RMSNORM, h_in,

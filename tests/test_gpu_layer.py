@@ -278,3 +278,38 @@ def test_7b_layer_full_size_stage_by_stage(ctx):
         got = st.sets[0].fetch(p, ks[p])
         _exact_topk_property(xs[p], got, ks[p])
         assert _sets_close(got, tr.idx[p], tr.x[p]), p
+
+
+@pytest.mark.parametrize("sp", [50, 70])
+def test_layer_q4_weights(ctx, sp):
+    """4-bit group-32 weights: the device packer's bits feed the GPU, the oracle quantises
+    the same fp16 matrices with its own quantiser (bit-equality of the two is checked in
+    test_gpu_q4), then the layer is compared as in the fp16 case."""
+    shape = S.MODEL_SHAPES["tiny_gqa"]
+    layers, kv, h = _host_stack(shape, 1, seed=5)
+    ks = _ks(shape, sp)
+    wq = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in layers[0].items()}
+    tr = O.decode_layer(_ocfg(shape), wq, h, kv[0][0].copy(), kv[0][1].copy(), KV_LEN, KV_LEN,
+                        O.SelectCfg(O.SEL_TOPK, ks), weights_q4=True)
+    st = _dev_stack(ctx, shape, layers, kv, kind=B.AF_W_Q4G32)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    # forced sets
+    st.sets[0].load(tr.idx)
+    st.layer(0, hin, hout, KV_LEN, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+    ctx.synchronize()
+    t = _taps(ctx, shape)
+    assert O.rel_err(t["qkv"], tr.qkv) <= TOL
+    assert O.rel_err(t["gateup"], tr.gateup, 1.0) <= TOL
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= TOL
+    # own selection
+    st.layer(0, hin, hout, KV_LEN, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
+    ctx.synchronize()
+    t = _taps(ctx, shape)
+    xs = (t["x_qkv"], t["attn"], t["x_gateup"], t["x_down"])
+    same = True
+    for p in range(4):
+        got = st.sets[0].fetch(p, ks[p])
+        _exact_topk_property(xs[p], got, ks[p])
+        assert _sets_close(got, tr.idx[p], tr.x[p]), p
+        same &= np.array_equal(got, tr.idx[p])
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
