@@ -39,6 +39,81 @@ def gemv_bytes(k: int, out: int, residual: bool = False) -> int:
     return k * (out * 2 + 6) + out * 2 + (out * 2 if residual else 0)
 
 
+def union_bench(args, S, B, torch, np) -> int:
+    """Small-batch decode GEMVs of one layer over the union of the tokens' active sets."""
+    shape = S.MODEL_SHAPES[args.shape]
+    Bt, sp = args.union, args.sparsity
+    d, f, hd = shape.d_model, shape.d_ffn, shape.head_dim
+    ops = [("qkv", d, shape.qkv_out), ("o", shape.n_heads * hd, d), ("gateup", d, 2 * f), ("down", f, d)]
+    ctx = B.Context(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    mats, Xs, idxs = [], [], []
+    for name, n_in, out in ops:
+        W = (torch.randn((n_in, out), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.float16)
+        sc = S.channel_scales(0, n_in, shape.name, name)          # shared by the tokens of the batch
+        X = np.stack([S.activation(0, sc, shape.name, name, b) for b in range(Bt)])
+        Xd = torch.from_numpy(X).cuda()
+        k = keep_count(n_in, sp)
+        idx_b = torch.empty((Bt, k), dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        for b in range(Bt):
+            ctx.select_topk(Xd[b], k, idx_b[b])
+        ctx.synchronize()
+        mats.append(W); Xs.append(Xd); idxs.append(idx_b)
+
+    def step():
+        outs = []
+        for W, Xd, idx_b in zip(mats, Xs, idxs):
+            outs.append(ctx.sparse_gemv_union_f16(W, Xd, idx_b))
+        return outs
+
+    outs = step()
+    ctx.synchronize()
+    union_frac = [float(o[2].item()) / n_in for o, (_, n_in, _) in zip(outs, ops)]
+    union_bytes = sum(int(o[2].item()) * out * 2 for o, (_, _, out) in zip(outs, ops))
+    for _ in range(args.warmup):
+        step()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # the widest operator alone, with events
+    W, Xd, idx_b = mats[2], Xs[2], idxs[2]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(ctx.stream)
+    for _ in range(20):
+        ctx.sparse_gemv_union_f16(W, Xd, idx_b)
+    e1.record(ctx.stream)
+    ctx.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / 20
+    alg = int(outs[2][2].item()) * ops[2][2] * 2 + Bt * (ops[2][1] * 2 + ops[2][1] // 8) + Bt * ops[2][2] * 2
+    achieved = alg / (us * 1e-6) / 1e9
+    out = {
+        "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+        "value": round(Bt * args.steps / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{args.shape}-shape layer, union small-batch GEMVs (qkv, o, gate|up, down), "
+                               f"B={Bt} tokens, {sp}% sparsity per token, GEMVs only",
+                   "B": Bt, "union_fraction_of_channels": [round(u, 4) for u in union_frac]},
+        "union_weight_bytes_per_step": union_bytes,
+        "union_weight_GBps": round(union_bytes * args.steps / dt / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "union_build_kernel + gemv_union_kernel (gate|up)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": alg, "us_per_launch": round(us, 3), "launches": 20},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +126,10 @@ def main() -> int:
     ap.add_argument("--group", type=int, default=1, help="cross-layer reuse group (1 = none)")
     ap.add_argument("--reuse-points", type=lambda s: int(s, 0), default=0b1111)
     ap.add_argument("--kv-len", type=int, default=512)
+    ap.add_argument("--overlap", action="store_true",
+                    help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
+    ap.add_argument("--union", type=int, default=0, metavar="B",
+                    help="small-batch union GEMV over the four operators of one layer of --shape (e.g. 70b) with B tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     args = ap.parse_args()
@@ -69,6 +148,9 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
+
+    if args.union:
+        return union_bench(args, S, B, torch, np)
 
     base = S.MODEL_SHAPES[args.shape]
     L = args.layers or base.n_layers
@@ -219,6 +301,45 @@ def main() -> int:
         if err > 2e-3:
             print(f"bench.py: WARNING layer-0 output differs from the oracle: {err}", file=sys.stderr)
 
+    overlap = None
+    if args.group > 1 and args.overlap:
+        # eager, untimed: every layer with taps; followers carry the leader's sets, and the set
+        # their own input would have selected is computed next to it for comparison
+        tap_of = (0, 2, 4, 6)
+        sums = [[0.0, 0] for _ in range(4)]
+        per_layer = []
+        cur = hin.clone()
+        nxt = torch.zeros_like(cur)
+        for l in range(L):
+            lead = l - l % args.group
+            follower = l != lead
+            mask = args.reuse_points if follower else 0
+            if follower:
+                for p in range(4):
+                    if mask >> p & 1:
+                        st.sets[l].idx[p].copy_(st.sets[lead].idx[p])
+                torch.cuda.synchronize()
+            st.layer(l, cur, nxt, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=mask))
+            ctx.synchronize()
+            row = [None] * 4
+            if follower:
+                for p in range(4):
+                    if not (mask >> p & 1):
+                        continue
+                    x = ctx.layer_tap(tap_of[p], widths[p])
+                    own = ctx.select_topk(x, ks[p])
+                    ctx.synchronize()
+                    inter = torch.isin(st.sets[l].idx[p][: ks[p]], own).sum().item()
+                    row[p] = inter / ks[p]
+                    sums[p][0] += row[p]
+                    sums[p][1] += 1
+            per_layer.append(row)
+            cur, nxt = nxt, cur
+        overlap = {"points": ["qkv", "o", "gateup", "down"],
+                   "mean": [round(a / n, 4) if n else None for a, n in sums],
+                   "layer1": per_layer[1] if L > 1 else None,
+                   "last_follower": per_layer[L - 1] if (L - 1) % args.group else per_layer[L - 2]}
+
     wl = f"{args.shape}-shape decoder stack, {L} layers, batch-1 decode, {args.weights} weights, " \
          f"{sp}% sparsity at qkv/o/gate-up/down, {kv_len}-token KV cache"
     if args.group > 1:
@@ -238,6 +359,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if overlap is not None:
+        out["overlap_reused_vs_own"] = overlap
     print(json.dumps(out))
     if graph is not None:
         ctx.graph_destroy(graph)

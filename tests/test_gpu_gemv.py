@@ -180,3 +180,30 @@ def test_union_identical_tokens_and_b1_equals_single(ctx):
     Yh = to_host(Y)
     assert all(np.array_equal(Yh[0], Yh[b]) for b in range(4))
     assert O.rel_err(Yh[0], O.sparse_gemv(W, x, idx)) <= 1e-4
+
+
+@pytest.mark.parametrize("name,out,n,Bt", [("down", 8192, 28672, 8), ("gateup", 57344, 8192, 4)])
+def test_union_70b_shapes_sampled(ctx, name, out, n, Bt):
+    """Widest input (28672) and widest output (57344) of the 70B-shape layer: the union is
+    compared bit-for-bit, sampled output columns against the oracle for every token."""
+    W = S.weight_matrix(0, out, n, "70b-union", name, threads=8)
+    sc = S.channel_scales(0, n, "70b-union", name)
+    X = np.stack([S.activation(0, sc, "70b-union", name, b) for b in range(Bt)])
+    k = O.keep_count(n, 50)
+    idx_b = np.stack([O.select_topk(X[b], k) for b in range(Bt)])
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    Y, U, un = ctx.sparse_gemv_union_f16(Wt, to_dev(X), to_dev(idx_b), y_kind=B.AF_F32)
+    ctx.synchronize()
+    Uo = O.union_indices(list(idx_b))
+    assert int(to_host(un)[0]) == len(Uo) and np.array_equal(to_host(U)[: len(Uo)], Uo)
+    assert k < len(Uo) < n                      # shared channel scales: tokens overlap but differ
+    rows = np.random.default_rng(1).choice(out, size=48, replace=False)
+    ref = O.union_gemv(W[rows], X, list(idx_b))
+    Yh = to_host(Y)
+    for b in range(Bt):
+        assert np.max(np.abs(Yh[b][rows] - ref[b])) <= 1e-4 * np.sqrt(np.mean(ref[b] ** 2)), b
+    # per-token selection on the GPU gives the same sets the union was built from
+    for b in (0, Bt - 1):
+        got = ctx.select_topk(to_dev(X[b]), k)
+        ctx.synchronize()
+        assert np.array_equal(to_host(got), idx_b[b])

@@ -313,3 +313,46 @@ def test_layer_q4_weights(ctx, sp):
         assert _sets_close(got, tr.idx[p], tr.x[p]), p
         same &= np.array_equal(got, tr.idx[p])
     assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
+
+
+def test_13b_shape_reuse_pair(ctx):
+    """13B-shape layers (d 5120, ffn 13824, 40 heads), one reuse group of two: the follower
+    runs with the leader's sets.  Each layer is fed the oracle's hidden state and the oracle's
+    sets; the stack entry point then runs free and its leader sets are compared."""
+    shape = S.MODEL_SHAPES["13b"]
+    kv_len, kv_cap = 512, 528
+    layers, kv, h = _host_stack(shape, 2, seed=6, kv_len=kv_len, kv_cap=kv_cap, threads=8)
+    for sp in (30, 70):
+        ks = _ks(shape, sp)
+        Ks = [k.copy() for k, _ in kv]; Vs = [v.copy() for _, v in kv]
+        traces, ov = O.decode_stack(_ocfg(shape), layers, h, Ks, Vs, kv_len, kv_len,
+                                    O.SelectCfg(O.SEL_TOPK, ks), group=2, reuse_points=0b1111,
+                                    want_overlap=True)
+        assert all(np.array_equal(traces[1].idx[p], traces[0].idx[p]) for p in range(4))
+        st = _dev_stack(ctx, shape, layers, kv, kv_cap=kv_cap)
+        hout = torch.zeros(shape.d_model, dtype=torch.float16, device="cuda")
+        hin_o = h
+        for l in range(2):
+            st.sets[l].load(traces[l].idx)
+            st.layer(l, to_dev(hin_o), hout, kv_len, kv_len,
+                     M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+            ctx.synchronize()
+            assert O.rel_err(to_host(hout), traces[l].hidden, 1.0) <= TOL, (sp, l)
+            hin_o = traces[l].hidden
+        st2 = _dev_stack(ctx, shape, layers, kv, kv_cap=kv_cap)
+        out = st2.run(to_dev(h), kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks), group=2,
+                      reuse_points=0b1111)
+        ctx.synchronize()
+        assert np.array_equal(st2.sets[0].fetch(0, ks[0]), traces[0].idx[0])     # same input bits
+        same = True
+        for p in range(4):
+            got = st2.sets[0].fetch(p, ks[p])
+            assert _sets_close(got, traces[0].idx[p], traces[0].x[p]), (sp, p)
+            same &= np.array_equal(got, traces[0].idx[p])
+        got_h, ref_h = to_host(out).astype(np.float64), traces[1].hidden.astype(np.float64)
+        if same:
+            assert O.rel_err(got_h, ref_h, 1.0) <= 2 * TOL
+        else:   # a channel at the k-th magnitude went the other way: close, not equal
+            cos = got_h @ ref_h / np.linalg.norm(got_h) / np.linalg.norm(ref_h)
+            assert cos > 0.9995, (sp, cos)
+        print(f"13b sp={sp}: oracle overlap of the follower {ov[1]}, leader sets identical: {same}")
