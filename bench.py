@@ -24,9 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs (FETCH_SIZE and
-# WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
-TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per launch of the dominant kernel (fused gate|up GEMV, 7B shape, 50 %) from the
+# two rocprofv3 --pmc runs summarised in profiles/gateup_7b_f16_sp50_pmc_traffic.md:
+# FETCH_SIZE 44300.0 KiB x 2.000 + WRITE_SIZE 239.1 KiB x 1.000, the factors being what the same
+# counters read for a plain 256 MiB device copy (131083.5 and 262144.0 KiB).
+TRAFFIC_BYTES_PER_LAUNCH = {("7b", "f16", 50): int((44300.0 * 2.0 + 239.1) * 1024)}
 
 
 def keep_count(n: int, sp: int) -> int:
@@ -130,6 +132,9 @@ def main() -> int:
                     help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
     ap.add_argument("--union", type=int, default=0, metavar="B",
                     help="small-batch union GEMV over the four operators of one layer of --shape (e.g. 70b) with B tokens")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies (float4 per lane), the known-size "
+                         "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     args = ap.parse_args()
@@ -176,6 +181,14 @@ def main() -> int:
     hin = torch.from_numpy(h_host).cuda()
     torch.cuda.synchronize()
     t_build = time.time() - t_build
+
+    if args.pmc_calibration:
+        ca = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
 
     sel = M.select_cfg(B.AF_SEL_TOPK, ks)
     run = lambda: st.run(hin, kv_len, kv_len, sel, group=args.group, reuse_points=args.reuse_points)
@@ -256,7 +269,8 @@ def main() -> int:
     achieved = alg / (us_per_launch * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": kname,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.shape, args.weights, sp)) if L == base.n_layers and args.group == 1 else None,
                 "bytes_per_launch": alg, "us_per_launch": round(us_per_launch, 3), "launches": launches}
 
     # ---- CPU oracle on a bounded sample ------------------------------------------------
