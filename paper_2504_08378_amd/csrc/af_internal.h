@@ -19,7 +19,6 @@ struct af_ws_layout {
   size_t attn_part;     // float[attn_floats]: per-(head, key split) softmax partials
   size_t act[7];        // fp16 inter-operator tensors of a layer (see af_layer_tap)
   size_t union_x;       // fp16 [max_in][8]: masked, transposed token values of the union GEMV
-  size_t union_flag;    // int32 [max_in]
   size_t total;
   size_t partial_floats;
   size_t attn_floats;
@@ -50,24 +49,6 @@ static inline int af_hip(hipError_t e) { return e == hipSuccess ? AF_OK : AF_EHI
   } while (0)
 
 // ---- internal launchers (host) -----------------------------------------------------------
-// Selection over an fp16 vector with an optional fused producer:
-//   AF_PRO_NONE    x = src
-//   AF_PRO_RMSNORM x = fp16(src * rsqrt(mean(src^2) + eps) * gain); x is also stored to x_out
-//   AF_PRO_SILUMUL x = fp16(silu(src[j]) * src[n + j]);             x is also stored to x_out
-struct af_select_args {
-  const half_t* src;
-  const half_t* gain;  // rmsnorm only
-  half_t* x_out;       // producer output (may be null for AF_PRO_NONE)
-  int n;
-  float eps;
-  int mode;            // AF_SEL_TOPK | AF_SEL_THRESHOLD | AF_SEL_DENSE (producer only)
-  int k;
-  float t;
-  int32_t* idx;
-  int32_t* count;      // may be null
-};
-int af_launch_select(af_ctx* ctx, int producer, const af_select_args& a);
-
 enum { AF_ROWS_GIVEN = 3 };  // rows come from memory (idx list) or are all channels (dense)
 
 // Where a fused GEMV gets its input vector and its rows from (see row_prologue.h).

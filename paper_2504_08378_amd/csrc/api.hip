@@ -23,8 +23,6 @@ af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
   }
   L.union_x = off;
   off = af_align(off + (size_t)max_in * 8 * sizeof(half_t));
-  L.union_flag = off;
-  off = af_align(off + (size_t)max_in * sizeof(int));
   L.total = off;
   return L;
 }

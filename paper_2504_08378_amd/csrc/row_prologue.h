@@ -175,6 +175,7 @@ struct RowPrologue {
   // Select on xs[0..n) (n % 8 == 0) and keep the entries of split s of S in list[] as
   // (index << 16 | fp16 bits).  Returns the number of entries kept by this workgroup;
   // *nidx_total is the size of the whole index set.  `hist` is RP_SCRATCH_WORDS words of LDS.
+  // `list` may be null (only idx_out / count_out are wanted).
   // Every thread owns a contiguous run of 8-element vectors, read from LDS 16 bytes at a
   // time in each pass; the thread order is therefore the index order.
   static __device__ __forceinline__ int select_split(const af_row_src& r, const unsigned short* xs,
@@ -265,7 +266,7 @@ struct RowPrologue {
           eq_seen += is_eq;
           if (keep & ((int)pos >= r0) & ((int)pos < r1)) {
             const int j = v * 8 + c;
-            list[pos - r0] = ((unsigned)j << 16) | bits;
+            if (list != nullptr) list[pos - r0] = ((unsigned)j << 16) | bits;
             if (to_mem) r.idx_out[pos] = j;
           }
           pos += keep;
