@@ -174,7 +174,7 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
                           int* nw_out, int* s_out) {
   // Measured on the 7B operators (cold matrices): 128-column tiles (256 B per row and
   // workgroup) win up to ~16K columns, 256-column tiles beyond.  A kernel that selects for
-  // itself repeats the selection in every workgroup, so it runs few, large workgroups
+  // itself (or builds its input vector) repeats that work in every workgroup, so it runs few, large workgroups
   // (one per CU); a plain GEMV prefers several small ones per CU.
   int lx = out <= 16384 ? 16 : 32;
   int nw = selects ? 16 : 4;
@@ -236,7 +236,7 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   // on the device)
   int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
   int lx, nw, S;
-  choose_config(ctx, a.out, max_rows, r.sel != AF_ROWS_GIVEN, &lx, &nw, &S);
+  choose_config(ctx, a.out, max_rows, r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, &lx, &nw, &S);
   const int tw = lx * 8;
   const int tiles = (a.out + tw - 1) / tw;
   const int out_pad = tiles * tw;
