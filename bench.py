@@ -273,6 +273,23 @@ def main() -> int:
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.shape, args.weights, sp)) if L == base.n_layers and args.group == 1 else None,
                 "bytes_per_launch": alg, "us_per_launch": round(us_per_launch, 3), "launches": launches}
 
+    # ---- the box's plain streaming-read rate (what an ideal reader of these bytes gets) ----
+    probe = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")
+    sink = ctx.probe_sink()
+    torch.cuda.synchronize()
+    stream_gbps = 0.0
+    for wgs in (4, 8, 16, 32):                      # the best launch shape of the plain reader
+        ctx.probe_stream_read(probe, sink, wgs)
+        e0.record(ctx.stream)
+        for _ in range(4):
+            ctx.probe_stream_read(probe, sink, wgs)
+        e1.record(ctx.stream)
+        ctx.synchronize()
+        stream_gbps = max(stream_gbps, 4 * probe.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del probe
+    roofline["measured_stream_read_GBps"] = round(stream_gbps, 1)
+    roofline["frac_of_measured_stream_read"] = round(achieved / stream_gbps, 4)
+
     # ---- CPU oracle on a bounded sample ------------------------------------------------
     cpu = None
     if host_layer0 is not None:

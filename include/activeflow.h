@@ -198,6 +198,16 @@ int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
  * 3 h_mid [d], 4 x_gateup [d], 5 gateup [2*ffn], 6 x_down [ffn].  fp16. */
 int af_layer_tap(af_ctx* ctx, int which, const void** dev_ptr);
 
+/* Measurement aid (the Eq. 4 memory-bandwidth term BW_mem of this device): one plain
+ * streaming-read kernel over `bytes` of device memory at dev_ptr (16-byte aligned; bytes a
+ * multiple of 16) with 16-byte loads, queued on the context's stream, in a grid of
+ * wgs_per_cu (1..32) 256-thread workgroups per compute unit.  Every workgroup stores one
+ * float fold of what it read to sink_f32 (device, af_probe_sink_floats() floats), so no
+ * load can be dropped.  The caller times it with events. */
+int af_probe_sink_floats(af_ctx* ctx);
+int af_probe_stream_read(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
+                         int wgs_per_cu);
+
 /* Stream capture helpers: record the calls made between begin and end into a HIP graph
  * and replay it.  The graph holds the pointers and scalars of the recorded calls. */
 typedef struct af_graph af_graph;

@@ -26,7 +26,7 @@ EXPORTS = [
     "af_set_workspace", "af_select_topk", "af_select_threshold", "af_pack_inmajor_f16",
     "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_select_gemv_f16", "af_sparse_gemv_union_f16",
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
-    "af_graph_launch", "af_graph_destroy",
+    "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
 ]
 
 
@@ -96,6 +96,8 @@ def lib() -> C.CDLL:
         "af_capture_end": (i, [vp, C.POINTER(vp)]),
         "af_graph_launch": (i, [vp, vp]),
         "af_graph_destroy": (i, [vp]),
+        "af_probe_sink_floats": (i, [vp]),
+        "af_probe_stream_read": (i, [vp, vp, sz, vp, i]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -312,3 +314,16 @@ class Context:
 
     def graph_destroy(self, g):
         _check(lib().af_graph_destroy(g), "af_graph_destroy")
+
+    # ---- measurement -----------------------------------------------------------------
+    def probe_sink(self):
+        return torch.zeros(lib().af_probe_sink_floats(self._h), dtype=torch.float32,
+                           device=self.device)
+
+    def probe_stream_read(self, buf, sink, wgs_per_cu: int = 8, offset: int = 0,
+                          nbytes: int | None = None):
+        """Queue one plain streaming read of buf[offset:offset+nbytes] (a uint8 CUDA tensor)."""
+        nbytes = buf.numel() - offset if nbytes is None else nbytes
+        _check(lib().af_probe_stream_read(self._h, C.c_void_p(_ptr(buf, torch.uint8).value + offset),
+                                          nbytes, _ptr(sink, torch.float32), wgs_per_cu),
+               "af_probe_stream_read")

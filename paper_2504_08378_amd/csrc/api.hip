@@ -171,6 +171,42 @@ extern "C" int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, v
   return AF_OK;
 }
 
+// ---- bandwidth probe ---------------------------------------------------------------------
+typedef float probe_f4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const probe_f4* __restrict__ p, size_t n16,
+                                                          float* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  probe_f4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    probe_f4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; i < n16; i += stride) acc += p[i];
+  float s = af_wave_sum(acc.x + acc.y + acc.z + acc.w);
+  if (threadIdx.x == 0) sink[blockIdx.x] = s;
+}
+
+extern "C" int af_probe_sink_floats(af_ctx* ctx) {
+  if (!ctx) return 0;
+  return ctx->n_cu * 32;
+}
+
+extern "C" int af_probe_stream_read(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
+                                    int wgs_per_cu) {
+  if (!ctx || !dev_ptr || !sink_f32) return AF_ENULL;
+  if (wgs_per_cu < 1 || wgs_per_cu > 32) return AF_EINVAL;
+  if (bytes == 0 || bytes % 16 || ((uintptr_t)dev_ptr & 15u)) return AF_ESHAPE;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(ctx->n_cu * wgs_per_cu), dim3(256), 0, ctx->stream,
+                     (const probe_f4*)dev_ptr, bytes / 16, (float*)sink_f32);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
 // ---- graph capture -----------------------------------------------------------------------
 extern "C" int af_capture_begin(af_ctx* ctx) {
   if (!ctx) return AF_ENULL;

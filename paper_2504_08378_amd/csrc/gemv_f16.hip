@@ -62,7 +62,24 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   const int S = gridDim.y, s = blockIdx.y;
   const af_row_src& r = p.rows;
 
-  if (p.use_lds_x) RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x);
+  // Rows given and their number known on the host: fetch this thread's share of the first
+  // staging pass now, so that the index round trip overlaps the construction of x.
+  constexpr int PF = GEMV_LIST / GEMV_THREADS;
+  int pre[PF];
+  const bool prefetched = r.sel == AF_ROWS_GIVEN && r.idx != nullptr && r.nidx_dev == nullptr;
+  if (prefetched) {
+    const int R = (r.nidx_host + S - 1) / S;
+    const int r0 = min(s * R, r.nidx_host), r1 = min(r0 + R, r.nidx_host);
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int i = r0 + tid + u * GEMV_THREADS;
+      pre[u] = i < r1 ? r.idx[i] : 0;
+    }
+  }
+
+  if (p.use_lds_x)
+    RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
+                r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
 
   float acc[8];
 #pragma unroll
@@ -99,7 +116,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
-                                     blockIdx.x == 0 && s == 0, &nidx_total);
+                                     blockIdx.x == 0 && s == 0, &nidx_total, p.use_lds_x != 0);
     stream(cnt);
   } else {
     int nidx = r.nidx_host;
@@ -110,10 +127,22 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
     for (int base = r0; base < r1; base += GEMV_LIST) {
       const int cnt = min(GEMV_LIST, r1 - base);
       __syncthreads();
-      for (int i = tid; i < cnt; i += GEMV_THREADS) {
-        const int j = r.idx ? r.idx[base + i] : base + i;
-        const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
-        s_list[i] = ((unsigned)j << 16) | bits;
+      if (prefetched && base == r0) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+          const int i = tid + u * GEMV_THREADS;
+          if (i < cnt) {
+            const int j = pre[u];
+            const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
+            s_list[i] = ((unsigned)j << 16) | bits;
+          }
+        }
+      } else {
+        for (int i = tid; i < cnt; i += GEMV_THREADS) {
+          const int j = r.idx ? r.idx[base + i] : base + i;
+          const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
+          s_list[i] = ((unsigned)j << 16) | bits;
+        }
       }
       __syncthreads();
       stream(cnt);

@@ -82,7 +82,9 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   const int slot = wave * LY + ly;
   const af_row_src& r = p.rows;
 
-  if (p.use_lds_x) RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x);
+  if (p.use_lds_x)
+    RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
+                r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
 
   float yacc[8], acc[8];
 #pragma unroll
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
-                                     blockIdx.x == 0 && s == 0, &nidx_total);
+                                     blockIdx.x == 0 && s == 0, &nidx_total, p.use_lds_x != 0);
     stream(cnt);
   } else {
     int nidx = r.nidx_host;
@@ -228,7 +230,9 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   const int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
   // a lane covers 8 columns = 4 bytes of a packed row; tiles of 8*LX columns
   int lx = a.out <= 4096 ? 16 : (a.out <= 16384 ? 32 : 64);
-  int nw = selects ? 16 : 4;
+  // one 1024-thread workgroup per compute unit measured faster than four 256-thread ones for
+  // every form of this kernel (with or without the selecting front end)
+  int nw = 16;
   if (const char* e = getenv("AF_Q4_LX")) {
     int v = atoi(e);
     if (v == 16 || v == 32 || v == 64) lx = v;

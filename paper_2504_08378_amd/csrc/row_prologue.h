@@ -19,14 +19,28 @@ struct RowPrologue {
     unsigned merged[256];
     unsigned wave_tot[WAVES];
     float red[WAVES];
-    unsigned digit, above, total;
+    unsigned digit, above;
   };
+
+  // Histogram scratch: RP_HIST_COPIES replicas, replica-major (replica r of bin b at
+  // r * 256 + b): lanes of one replica that hit different bins hit different banks, and the
+  // merge reads 256 consecutive words per replica.  First 256-bin table at word 0, the
+  // 128-bin table of the second digit behind it.
+  static constexpr int H1 = 0;
+  static constexpr int H2 = 256 * RP_HIST_COPIES;
+
+  static __device__ __forceinline__ void zero_hist(unsigned* hist) {
+    for (int i = threadIdx.x; i < RP_SCRATCH_WORDS; i += THREADS) hist[i] = 0;
+  }
 
   // Fill xs[0..n) with the fp16 bits of the operator input (n % 8 == 0).  Global reads are
   // 16-byte vectors issued four at a time, so a thread waits for memory once per batch and
   // not once per element.
+  // `hist`, when given, is cleared on the way (select_split is then told so), which saves the
+  // selection a barrier.
   static __device__ __forceinline__ void produce(const af_row_src& r, unsigned short* xs, Smem& sm,
-                                                 bool store_x, int store_phase, int store_stride) {
+                                                 bool store_x, int store_phase, int store_stride,
+                                                 unsigned* hist = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = r.n, nvec = n >> 3;
     constexpr int B = 4;
@@ -46,11 +60,20 @@ struct RowPrologue {
       }
     } else if (r.pro == AF_PRO_RMSNORM) {
       const half8* gain = reinterpret_cast<const half8*>(r.gain);
+      // When one batch per thread covers the vector (the usual case) the gains are fetched
+      // together with the source, so the sum-of-squares reduction does not sit between two
+      // dependent global round trips.
+      const bool single = nvec <= B * THREADS;
+      half8 g[B];
       float ss = 0.f;
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
         half8 t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
+        if (single) {
+#pragma unroll
+          for (int u = 0; u < B; ++u) g[u] = (v0 + u * THREADS < nvec) ? gain[v0 + u * THREADS] : zero;
+        }
 #pragma unroll
         for (int u = 0; u < B; ++u) {
 #pragma unroll
@@ -66,9 +89,10 @@ struct RowPrologue {
       for (int w = 0; w < WAVES; ++w) tot += sm.red[w];
       const float scale = 1.0f / sqrtf(tot / (float)n + r.eps);
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
-        half8 g[B];
+        if (!single) {
 #pragma unroll
-        for (int u = 0; u < B; ++u) g[u] = (v0 + u * THREADS < nvec) ? gain[v0 + u * THREADS] : zero;
+          for (int u = 0; u < B; ++u) g[u] = (v0 + u * THREADS < nvec) ? gain[v0 + u * THREADS] : zero;
+        }
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           if (v0 + u * THREADS < nvec) {
@@ -103,22 +127,12 @@ struct RowPrologue {
         }
       }
     }
+    if (hist != nullptr) zero_hist(hist);
     __syncthreads();
     if (store_x && r.x_out != nullptr) {
       half8* dst = reinterpret_cast<half8*>(r.x_out);
       for (int v = store_phase * THREADS + tid; v < nvec; v += store_stride * THREADS) dst[v] = xv[v];
     }
-  }
-
-  // Histogram scratch: RP_HIST_COPIES replicas, replica-major (replica r of bin b at
-  // r * 256 + b): lanes of one replica that hit different bins hit different banks, and the
-  // merge reads 256 consecutive words per replica.  First 256-bin table at word 0, the
-  // 128-bin table of the second digit behind it.
-  static constexpr int H1 = 0;
-  static constexpr int H2 = 256 * RP_HIST_COPIES;
-
-  static __device__ __forceinline__ void zero_hist(unsigned* hist) {
-    for (int i = threadIdx.x; i < RP_SCRATCH_WORDS; i += THREADS) hist[i] = 0;
   }
 
   // digit d with count(digit > d) < want <= count(digit >= d); result in sm.digit / sm.above
@@ -154,8 +168,9 @@ struct RowPrologue {
     __syncthreads();
   }
 
-  // exclusive prefix over the workgroup in thread order; total left in sm.total
-  static __device__ __forceinline__ unsigned excl_scan(unsigned v, Smem& sm) {
+  // exclusive prefix over the workgroup in thread order; *total gets the sum over all threads.
+  // sm.wave_tot must not be rewritten before the next barrier of the caller.
+  static __device__ __forceinline__ unsigned excl_scan(unsigned v, Smem& sm, unsigned* total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned inc = af_wave_incl_scan(v);
     if (lane == 63) sm.wave_tot[wave] = inc;
@@ -167,8 +182,7 @@ struct RowPrologue {
       if (w < wave) base += t;
       tot += t;
     }
-    if (threadIdx.x == 0) sm.total = tot;
-    __syncthreads();
+    *total = tot;
     return base + inc - v;
   }
 
@@ -181,7 +195,7 @@ struct RowPrologue {
   static __device__ __forceinline__ int select_split(const af_row_src& r, const unsigned short* xs,
                                                      unsigned* hist, Smem& sm, unsigned* list,
                                                      int S, int s, bool store_idx, bool store_count,
-                                                     int* nidx_total) {
+                                                     int* nidx_total, bool hist_zeroed = false) {
     typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
     const int tid = threadIdx.x, lane = tid & 63;
     const int nvec = r.n >> 3;
@@ -209,8 +223,10 @@ struct RowPrologue {
       }
     }
     if (topk && r.k > 0) {
-      zero_hist(hist);
-      __syncthreads();
+      if (!hist_zeroed) {
+        zero_hist(hist);
+        __syncthreads();
+      }
       for (int v = v0; v < v1; ++v) {
         const u16x8 b = xv[v];
 #pragma unroll
@@ -243,8 +259,8 @@ struct RowPrologue {
         eq += (int)key == T;
       }
     }
-    const unsigned pre = excl_scan(gt | (eq << 16), sm);
-    const unsigned tot = sm.total;
+    unsigned tot;
+    const unsigned pre = excl_scan(gt | (eq << 16), sm, &tot);
     const int nidx = (int)((tot & 0xFFFFu) + min(tot >> 16, quota));
     *nidx_total = nidx;
     const int R = (nidx + S - 1) / S;
