@@ -11,7 +11,7 @@ What it follows (ActiveFlow, arXiv 2504.08378):
     activations of largest magnitude take part in the product; the paper states
     the rule both as top-k and as "magnitude above a threshold" (Section 6,
     "Caching", keeps one threshold per sparsity level) -> select_topk,
-    select_threshold.
+    select_threshold, calibrate_threshold.
   * Section 4, pipeline operations T and C: T turns the activation into the
     indices of the active weight channels; C computes the operator on those
     channels only.  Because the result is exactly W (x * mask), the oracle
@@ -84,6 +84,29 @@ def select_threshold(x, t: float) -> np.ndarray:
     """{j : |x_j| > t}, compared in fp32 (fp16 -> fp32 is exact), ascending int32."""
     mag = np.abs(np.asarray(x, dtype=np.float16).astype(np.float32))
     return np.nonzero(mag > np.float32(t))[0].astype(np.int32)
+
+
+def calibrate_threshold(samples, sparsity_percent: int) -> float:
+    """Threshold of one operator for one sparsity level (Section 6, "Caching": the
+    index kernel keeps one activation threshold per sparsity level and compares
+    against it; Section 2.1 calls the result Top-K sparsity, so the threshold
+    stands for the top-k rule on typical inputs).
+
+    The paper does not say how the thresholds are found.  Reading taken: pool the
+    magnitudes of a calibration stream of the operator's input vectors (NaN left
+    out), N values; with m = keep_count(N, sp) the threshold is the (m+1)-th
+    largest pooled magnitude, so that the strict rule |x| > t keeps at most m of
+    the pooled values -- exactly the pooled top-m when no value ties with the
+    boundary.  m == N (nothing to drop) gives -1.0, which every magnitude exceeds.
+    The value returned is an fp16 magnitude (or -1.0), exact in fp32."""
+    mags = np.concatenate([np.abs(np.asarray(v, dtype=np.float16).astype(np.float64)).ravel()
+                           for v in samples]) if len(samples) else np.zeros(0)
+    mags = mags[~np.isnan(mags)]
+    N = mags.size
+    m = keep_count(N, sparsity_percent)
+    if m >= N:
+        return -1.0
+    return float(np.sort(mags)[::-1][m])
 
 
 # --------------------------------------------------------------------------
@@ -338,11 +361,15 @@ def decode_stack(cfg: LayerCfg, layers: list, hidden, Ks: list, Vs: list, kv_len
     l with l % group == 0 selects; the other layers of its group reuse its sets at
     the points whose bit is set in reuse_points.  Returns (traces, overlap) where
     overlap[l][p] compares the set used with the set the layer's own input would
-    have selected (None for points that selected themselves or when not wanted)."""
+    have selected (None for points that selected themselves or when not wanted).
+    `sel` is one SelectCfg for all layers or a list with one per layer (calibrated
+    thresholds differ from operator to operator)."""
     traces, ov = [], []
     sets = [None] * 4
     h = hidden
+    per_layer = sel if isinstance(sel, (list, tuple)) else [sel] * len(layers)
     for l, w in enumerate(layers):
+        sel = per_layer[l]
         follower = group > 1 and (l % group) != 0
         mask = sel.reuse_mask | (reuse_points if follower else 0)
         s = SelectCfg(sel.mode, sel.k, sel.t, mask)
