@@ -198,6 +198,29 @@ int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
  * 3 h_mid [d], 4 x_gateup [d], 5 gateup [2*ffn], 6 x_down [ffn].  fp16. */
 int af_layer_tap(af_ctx* ctx, int which, const void** dev_ptr);
 
+/* ---- threshold calibration (Section 6, "Caching": the index kernel keeps one activation
+ * threshold per sparsity level; the paper does not say how they are found) ----------------
+ * Reading built here: pool the magnitudes of a calibration stream of one operator's input
+ * vectors in an exact histogram over the 15-bit fp16 magnitude key (NaN left out); for
+ * sparsity sp with N pooled values, m = N - floor(sp*N/100) are to be kept and the threshold
+ * is the (m+1)-th largest pooled magnitude, so the strict rule |x| > t keeps at most m of
+ * them (exactly the pooled top-m when nothing ties with the boundary); m == N gives -1.
+ *   af_calib_accumulate        adds the n values of x (device fp16) to hist (device,
+ *                              AF_CALIB_BINS uint32 counters, zeroed by the caller before the
+ *                              first call; a counter wraps at 2^32).
+ *   af_calib_accumulate_layer  adds the four operator inputs of the most recent
+ *                              af_decode_layer call on this context (x_qkv, attn, x_gateup,
+ *                              x_down) to hist[0..3] (host array of four device pointers).
+ *   af_calib_thresholds        writes the thresholds of n_levels <= AF_CALIB_MAX_LEVELS
+ *                              sparsity levels (host int array, percent 0..100) to t_out
+ *                              (device, n_levels floats; each an fp16 magnitude or -1). */
+#define AF_CALIB_BINS 32768
+#define AF_CALIB_MAX_LEVELS 16
+int af_calib_accumulate(af_ctx* ctx, const void* x_f16, int n, uint32_t* hist);
+int af_calib_accumulate_layer(af_ctx* ctx, const af_layer_cfg* cfg, uint32_t* const* hist);
+int af_calib_thresholds(af_ctx* ctx, const uint32_t* hist, const int* sparsity_pct, int n_levels,
+                        float* t_out);
+
 /* Measurement aid (the Eq. 4 memory-bandwidth term BW_mem of this device): one plain
  * streaming-read kernel over `bytes` of device memory at dev_ptr (16-byte aligned; bytes a
  * multiple of 16) with 16-byte loads, queued on the context's stream, in a grid of

@@ -20,6 +20,7 @@ AF_W_F16, AF_W_Q4G32 = 0, 1
 AF_SEL_TOPK, AF_SEL_THRESHOLD, AF_SEL_DENSE = 0, 1, 2
 AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
+AF_CALIB_BINS = 32768
 
 EXPORTS = [
     "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
@@ -27,6 +28,7 @@ EXPORTS = [
     "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_select_gemv_f16", "af_sparse_gemv_union_f16",
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
     "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
+    "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
 ]
 
 
@@ -98,6 +100,9 @@ def lib() -> C.CDLL:
         "af_graph_destroy": (i, [vp]),
         "af_probe_sink_floats": (i, [vp]),
         "af_probe_stream_read": (i, [vp, vp, sz, vp, i]),
+        "af_calib_accumulate": (i, [vp, vp, i, vp]),
+        "af_calib_accumulate_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(vp)]),
+        "af_calib_thresholds": (i, [vp, vp, C.POINTER(C.c_int), i, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -314,6 +319,27 @@ class Context:
 
     def graph_destroy(self, g):
         _check(lib().af_graph_destroy(g), "af_graph_destroy")
+
+    # ---- threshold calibration ---------------------------------------------------------
+    def calib_hist(self):
+        return torch.zeros(AF_CALIB_BINS, dtype=torch.int32, device=self.device)
+
+    def calib_accumulate(self, x, hist):
+        _check(lib().af_calib_accumulate(self._h, _ptr(x, torch.float16, "x"), x.numel(),
+                                         _ptr(hist, torch.int32, "hist")), "af_calib_accumulate")
+
+    def calib_accumulate_layer(self, cfg: LayerCfg, hists):
+        arr = (C.c_void_p * 4)(*[_ptr(h, torch.int32, "hist").value for h in hists])
+        _check(lib().af_calib_accumulate_layer(self._h, C.byref(cfg), arr),
+               "af_calib_accumulate_layer")
+
+    def calib_thresholds(self, hist, sparsity_pct):
+        lv = (C.c_int * len(sparsity_pct))(*[int(v) for v in sparsity_pct])
+        out = torch.empty(len(sparsity_pct), dtype=torch.float32, device=self.device)
+        _check(lib().af_calib_thresholds(self._h, _ptr(hist, torch.int32, "hist"), lv,
+                                         len(sparsity_pct), _ptr(out, torch.float32)),
+               "af_calib_thresholds")
+        return out
 
     # ---- measurement -----------------------------------------------------------------
     def probe_sink(self):
