@@ -172,7 +172,14 @@ typedef struct {
   int k[4];            /* top-k mode: channels kept at each point        */
   float t[4];          /* threshold mode: threshold at each point        */
   unsigned reuse_mask; /* bit p set: do not select at p, use sets (Section 3) */
+  unsigned flags;      /* AF_SEL_SKIP_SETS or 0 */
 } af_select_cfg;
+/* AF_SEL_SKIP_SETS: a selecting point does not write its index set and count (the GEMV uses
+ * them on the fly) unless a later layer of the same af_decode_stack call reuses them; `sets`
+ * entries that are neither written nor read may then be NULL.  In threshold mode this is the
+ * fully fused form: each workgroup of the GEMV compares only the channels of its own range
+ * against the threshold (Section 6), and no index list is built for the whole vector. */
+enum { AF_SEL_SKIP_SETS = 1 };
 
 /* One batch-1 decode step of one layer.  hidden_in/hidden_out fp16 [d] (may alias).
  * k_cache/v_cache fp16 [n_kv][kv_cap][hd]; the new (rotated) key and the value are
@@ -186,11 +193,13 @@ int af_decode_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
 /* n_layers layers in sequence.  w, k_caches, v_caches, sets: host arrays of n_layers
  * entries.  With group > 1, layer l with l % group != 0 reuses the sets of its group's
  * first layer at the points named by reuse_points (Section 3, N = 4); sets[l] of a
- * follower is not touched at those points.  sel->reuse_mask applies to every layer. */
+ * follower is not touched at those points.  sel: n_sel configurations, n_sel == 1 (shared by
+ * all layers) or n_sel == n_layers (one per layer: calibrated thresholds differ from operator
+ * to operator); a configuration's reuse_mask applies on top of the group rule. */
 int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w, int n_layers,
                     const void* hidden_in, void* hidden_out, void* const* k_caches,
                     void* const* v_caches, int kv_len, int kv_cap, int pos,
-                    const af_select_cfg* sel, int group, unsigned reuse_points,
+                    const af_select_cfg* sel, int n_sel, int group, unsigned reuse_points,
                     af_idx_sets* sets);
 
 /* Device address of an inter-operator tensor of the most recent af_decode_layer call on

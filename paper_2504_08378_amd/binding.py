@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libactiveflow.so")
 AF_F16, AF_F32 = 0, 1
 AF_W_F16, AF_W_Q4G32 = 0, 1
 AF_SEL_TOPK, AF_SEL_THRESHOLD, AF_SEL_DENSE = 0, 1, 2
+AF_SEL_SKIP_SETS = 1
 AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
 AF_CALIB_BINS = 32768
@@ -56,7 +57,7 @@ class IdxSets(C.Structure):
 
 class SelectCfg(C.Structure):
     _fields_ = [("mode", C.c_int), ("k", C.c_int * 4), ("t", C.c_float * 4),
-                ("reuse_mask", C.c_uint)]
+                ("reuse_mask", C.c_uint), ("flags", C.c_uint)]
 
 
 _lib = None
@@ -91,7 +92,7 @@ def lib() -> C.CDLL:
         "af_decode_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, vp,
                                 i, i, i, C.POINTER(SelectCfg), C.POINTER(IdxSets)]),
         "af_decode_stack": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), i, vp, vp,
-                                C.POINTER(vp), C.POINTER(vp), i, i, i, C.POINTER(SelectCfg), i, u,
+                                C.POINTER(vp), C.POINTER(vp), i, i, i, C.POINTER(SelectCfg), i, i, u,
                                 C.POINTER(IdxSets)]),
         "af_layer_tap": (i, [vp, i, C.POINTER(vp)]),
         "af_capture_begin": (i, [vp]),
@@ -290,12 +291,17 @@ class Context:
             C.byref(sets) if sets is not None else None), "af_decode_layer")
 
     def decode_stack(self, cfg: LayerCfg, w_array, n_layers: int, hidden_in, hidden_out,
-                     k_ptrs, v_ptrs, kv_len: int, kv_cap: int, pos: int, sel: SelectCfg,
+                     k_ptrs, v_ptrs, kv_len: int, kv_cap: int, pos: int, sel,
                      group: int, reuse_points: int, sets_array):
+        """sel: one SelectCfg for all layers, or a sequence with one per layer."""
+        if isinstance(sel, SelectCfg):
+            sel_arr, n_sel = (SelectCfg * 1)(sel), 1
+        else:
+            sel_arr, n_sel = (SelectCfg * len(sel))(*sel), len(sel)
         _check(lib().af_decode_stack(
             self._h, C.byref(cfg), w_array, n_layers, _ptr(hidden_in, torch.float16, "hidden_in"),
             _ptr(hidden_out, torch.float16, "hidden_out"), k_ptrs, v_ptrs, kv_len, kv_cap, pos,
-            C.byref(sel), group, reuse_points, sets_array), "af_decode_stack")
+            sel_arr, n_sel, group, reuse_points, sets_array), "af_decode_stack")
 
     def layer_tap(self, which: int, n: int):
         """fp16 view (a copy) of an inter-operator tensor of the last decode_layer call."""

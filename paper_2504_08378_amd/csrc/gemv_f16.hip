@@ -29,6 +29,7 @@ struct GemvParams {
   void* y;
   const half_t* residual;
   int out, ld, y_kind, out_pad, use_lds_x;
+  int range_sel;  // threshold selection per channel range, no list for the whole vector
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
     }
   }
 
-  if (p.use_lds_x)
+  if (p.use_lds_x && !p.range_sel)
     RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
                 r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
 
@@ -113,7 +114,9 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
     }
   };
 
-  if (r.sel != AF_ROWS_GIVEN) {
+  if (p.range_sel) {
+    stream(RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
+  } else if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
                                      blockIdx.x == 0 && s == 0, &nidx_total, p.use_lds_x != 0);
@@ -271,12 +274,15 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
   // a selecting workgroup keeps its whole split in the staged list
-  if (r.sel != AF_ROWS_GIVEN) {
-    const int need = (max_rows + GEMV_LIST - 1) / GEMV_LIST;
-    if (S < need) S = need;
-  }
+  const bool range_sel = r.sel == AF_SEL_THRESHOLD && !r.idx_out && !r.count_out;
+  auto split_fits = [&](int s_try) {
+    if (r.sel == AF_ROWS_GIVEN) return true;
+    if (range_sel) return 8 * ((r.n / 8 + s_try - 1) / s_try) <= GEMV_LIST;
+    return (size_t)s_try * GEMV_LIST >= (size_t)max_rows;
+  };
+  while (!split_fits(S)) ++S;
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (r.sel != AF_ROWS_GIVEN && (size_t)S * GEMV_LIST < (size_t)max_rows) return AF_EWORKSPACE;
+  if (!split_fits(S)) return AF_EWORKSPACE;
   GemvParams p;
   p.W = (const half_t*)a.W;
   p.rows = r;
@@ -289,6 +295,7 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
   p.use_lds_x = (r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN) ? 1 : 0;
+  p.range_sel = range_sel ? 1 : 0;
   const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
   dim3 grid(tiles, S);
   if (lx == 64)

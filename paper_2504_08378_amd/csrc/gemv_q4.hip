@@ -28,6 +28,7 @@ struct Q4Params {
   void* y;
   const half_t* residual;
   int out, ld, y_kind, out_pad, use_lds_x;
+  int range_sel;  // threshold selection per channel range, no list for the whole vector
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   const int slot = wave * LY + ly;
   const af_row_src& r = p.rows;
 
-  if (p.use_lds_x)
+  if (p.use_lds_x && !p.range_sel)
     RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
                 r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
 
@@ -133,7 +134,9 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
     }
   };
 
-  if (r.sel != AF_ROWS_GIVEN) {
+  if (p.range_sel) {
+    stream(RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
+  } else if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
                                      blockIdx.x == 0 && s == 0, &nidx_total, p.use_lds_x != 0);
@@ -256,12 +259,15 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   if (S > max_s) S = max_s;
   if (S > 256) S = 256;
   if (S < 1) S = 1;
-  if (selects) {
-    const int need = (max_rows + Q4_LIST - 1) / Q4_LIST;
-    if (S < need) S = need;
-  }
+  const bool range_sel = r.sel == AF_SEL_THRESHOLD && !r.idx_out && !r.count_out;
+  auto split_fits = [&](int s_try) {  // a selecting workgroup keeps its whole split in the list
+    if (!selects) return true;
+    if (range_sel) return 8 * ((r.n / 8 + s_try - 1) / s_try) <= Q4_LIST;
+    return (size_t)s_try * Q4_LIST >= (size_t)max_rows;
+  };
+  while (!split_fits(S)) ++S;
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (selects && (size_t)S * Q4_LIST < (size_t)max_rows) return AF_EWORKSPACE;
+  if (!split_fits(S)) return AF_EWORKSPACE;
   Q4Params p;
   p.packed = (const unsigned char*)a.W;
   p.scales = a.scales;
@@ -275,6 +281,7 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
   p.use_lds_x = (r.pro != AF_PRO_NONE || selects) ? 1 : 0;
+  p.range_sel = range_sel ? 1 : 0;
   const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
   dim3 grid(tiles, S);
   if (lx == 64)

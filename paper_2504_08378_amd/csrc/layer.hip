@@ -308,12 +308,13 @@ static int check_layer_args(const af_ctx* ctx, const af_layer_cfg* cfg, const af
   return AF_OK;
 }
 
-// One layer.  `own` receives the sets of points that select here; `src` provides the sets of
-// points whose bit is set in reuse (own == src unless the layer follows a group leader).
+// One layer.  `own` receives the sets of the selecting points named in write_sets; `src`
+// provides the sets of points whose bit is set in reuse (own == src unless the layer follows
+// a group leader).
 static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
                      const half_t* h_in, half_t* h_out, void* kc, void* vc, int kv_len,
                      int kv_cap, int pos, const af_select_cfg* sel, unsigned reuse,
-                     const af_idx_sets* own, const af_idx_sets* src) {
+                     unsigned write_sets, const af_idx_sets* own, const af_idx_sets* src) {
   const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim;
   const int qdim = cfg->n_heads * hd, qkv_out = (cfg->n_heads + 2 * cfg->n_kv_heads) * hd;
   half_t* act[7];
@@ -332,8 +333,8 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
   for (int p = 0; p < 4; ++p) {
     const bool reused = (reuse >> p) & 1u;
     const af_idx_sets* ss = reused ? src : own;
-    if (sel->mode == AF_SEL_DENSE && !reused) {
-      pt[p] = {nullptr, widths[p], nullptr};
+    if (!reused && (sel->mode == AF_SEL_DENSE || !((write_sets >> p) & 1u))) {
+      pt[p] = {nullptr, widths[p], nullptr};  // not read: the point is dense or selects for itself
     } else if (sel->mode == AF_SEL_TOPK) {
       pt[p] = {ss->idx[p], sel->k[p], nullptr};
     } else {  // threshold, or a reused set under dense/threshold: the count lives on the device
@@ -368,8 +369,10 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
       r.sel = sel->mode;
       r.k = sel->k[p];
       r.t = sel->t[p];
-      r.idx_out = own->idx[p];
-      r.count_out = own->count[p];
+      if ((write_sets >> p) & 1u) {
+        r.idx_out = own->idx[p];
+        r.count_out = own->count[p];
+      }
     } else {
       r.sel = AF_ROWS_GIVEN;
       r.idx = pt[p].idx;
@@ -394,15 +397,15 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
 }
 
 static int check_layer_ptrs(const af_layer_cfg* cfg, const af_layer_weights* w,
-                            const af_select_cfg* sel, unsigned reuse, const af_idx_sets* own,
-                            const af_idx_sets* src) {
+                            const af_select_cfg* sel, unsigned reuse, unsigned write_sets,
+                            const af_idx_sets* own, const af_idx_sets* src) {
   if (!w->Wqkv || !w->Wo || !w->Wgateup || !w->Wdown || !w->g_attn_norm || !w->g_ffn_norm)
     return AF_ENULL;
   if (cfg->weight_kind == AF_W_Q4G32 && (!w->Sqkv || !w->So || !w->Sgateup || !w->Sdown))
     return AF_ENULL;
   for (int p = 0; p < 4; ++p) {
     const bool reused = (reuse >> p) & 1u;
-    if (!reused && sel->mode == AF_SEL_DENSE) continue;
+    if (!reused && (sel->mode == AF_SEL_DENSE || !((write_sets >> p) & 1u))) continue;
     const af_idx_sets* ss = reused ? src : own;
     if (!ss || !ss->idx[p]) return AF_ENULL;
     if (sel->mode != AF_SEL_TOPK && !ss->count[p]) return AF_ENULL;
@@ -418,43 +421,56 @@ extern "C" int af_decode_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_la
     return AF_ENULL;
   int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
   if (rc) return rc;
-  if ((rc = check_layer_ptrs(cfg, w, sel, sel->reuse_mask & 15u, sets, sets))) return rc;
+  static const af_idx_sets none = {};
+  const unsigned write_sets = (sel->flags & AF_SEL_SKIP_SETS) ? 0u : 15u;
+  const af_idx_sets* ss = sets ? sets : &none;
+  if ((rc = check_layer_ptrs(cfg, w, sel, sel->reuse_mask & 15u, write_sets, ss, ss))) return rc;
   return run_layer(ctx, cfg, w, (const half_t*)hidden_in, (half_t*)hidden_out, k_cache, v_cache,
-                   kv_len, kv_cap, pos, sel, sel->reuse_mask & 15u, sets, sets);
+                   kv_len, kv_cap, pos, sel, sel->reuse_mask & 15u, write_sets, ss, ss);
+}
+
+// Points of layer l whose freshly selected sets have to reach memory: all of them, unless the
+// configuration asks to skip sets nobody reads; then only what a follower of l reuses.
+static unsigned stack_write_sets(const af_select_cfg* sel, int l, int n_layers, int group,
+                                 unsigned reuse_points) {
+  if (!(sel->flags & AF_SEL_SKIP_SETS)) return 15u;
+  const bool leader_with_followers = group > 1 && (l % group) == 0 && l + 1 < n_layers;
+  return leader_with_followers ? (reuse_points & 15u) : 0u;
 }
 
 extern "C" int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w,
                                int n_layers, const void* hidden_in, void* hidden_out,
                                void* const* k_caches, void* const* v_caches, int kv_len,
-                               int kv_cap, int pos, const af_select_cfg* sel, int group,
+                               int kv_cap, int pos, const af_select_cfg* sel, int n_sel, int group,
                                unsigned reuse_points, af_idx_sets* sets) {
   if (!ctx || !cfg || !w || !hidden_in || !hidden_out || !k_caches || !v_caches || !sel)
     return AF_ENULL;
   if (n_layers <= 0 || group < 1) return AF_EINVAL;
-  int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
-  if (rc) return rc;
+  if (n_sel != 1 && n_sel != n_layers) return AF_EINVAL;
+  static const af_idx_sets none = {};
+  int rc;
   // validate every layer before the first launch
   for (int l = 0; l < n_layers; ++l) {
+    const af_select_cfg* sl = &sel[n_sel == 1 ? 0 : l];
+    if ((rc = check_layer_args(ctx, cfg, sl, kv_len, kv_cap, pos))) return rc;
     if (!k_caches[l] || !v_caches[l]) return AF_ENULL;
     const bool follower = group > 1 && (l % group) != 0;
-    const unsigned reuse = (sel->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
-    const af_idx_sets* own = sets ? &sets[l] : nullptr;
-    const af_idx_sets* src = sets ? &sets[follower ? l - l % group : l] : nullptr;
-    if (!own && sel->mode != AF_SEL_DENSE) return AF_ENULL;
-    if (!own && reuse) return AF_ENULL;
-    static const af_idx_sets none = {};
-    if ((rc = check_layer_ptrs(cfg, &w[l], sel, reuse, own ? own : &none, src ? src : &none)))
-      return rc;
+    const unsigned reuse = (sl->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
+    const unsigned write_sets = stack_write_sets(sl, l, n_layers, group, reuse_points);
+    const af_idx_sets* own = sets ? &sets[l] : &none;
+    const af_idx_sets* src = sets ? &sets[follower ? l - l % group : l] : &none;
+    if ((rc = check_layer_ptrs(cfg, &w[l], sl, reuse, write_sets, own, src))) return rc;
   }
   for (int l = 0; l < n_layers; ++l) {
+    const af_select_cfg* sl = &sel[n_sel == 1 ? 0 : l];
     const bool follower = group > 1 && (l % group) != 0;
-    const unsigned reuse = (sel->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
-    static const af_idx_sets none = {};
+    const unsigned reuse = (sl->reuse_mask | (follower ? reuse_points : 0u)) & 15u;
+    const unsigned write_sets = stack_write_sets(sl, l, n_layers, group, reuse_points);
     const af_idx_sets* own = sets ? &sets[l] : &none;
     const af_idx_sets* src = sets ? &sets[follower ? l - l % group : l] : &none;
     const half_t* hin = (const half_t*)(l == 0 ? hidden_in : hidden_out);
     rc = run_layer(ctx, cfg, &w[l], hin, (half_t*)hidden_out, k_caches[l], v_caches[l], kv_len,
-                   kv_cap, pos, sel, reuse, own, src);
+                   kv_cap, pos, sl, reuse, write_sets, own, src);
     if (rc) return rc;
   }
   return AF_OK;

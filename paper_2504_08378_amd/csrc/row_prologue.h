@@ -186,6 +186,163 @@ struct RowPrologue {
     return base + inc - v;
   }
 
+  // |x| > t as an integer test on the magnitude key: key > bits(largest fp16 <= t) for t >= 0;
+  // -1 lets every key pass for t < 0.  (NaN is kept out by the separate key <= 0x7C00 test.)
+  static __device__ __forceinline__ int threshold_key(float t) {
+    if (t < 0.f) return -1;
+    typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+    const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(t, 0.f);  // toward zero = downward for t >= 0
+    return (int)(__builtin_bit_cast(unsigned, h) & 0x7FFFu);
+  }
+
+  // Threshold selection without an index list for the whole vector (Section 6: a channel is
+  // active iff its magnitude passes the preloaded threshold, which needs no look at any other
+  // channel).  The channels are cut into S contiguous ranges of whole 8-element vectors;
+  // workgroup s builds x only for its range, in xs[0 .. 8 * vectors of the range), and lists
+  // the channels of that range that pass, as (index << 16 | fp16 bits).  RMSNorm still reads
+  // the whole source once for the sum of squares.  Returns the number of list entries.
+  // The caller guarantees 8 * ceil(n / 8 / S) <= capacity of `list`.
+  static __device__ __forceinline__ int threshold_range(const af_row_src& r, unsigned short* xs,
+                                                        Smem& sm, unsigned* list, int S, int s,
+                                                        bool store_x) {
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = r.n, nvec = n >> 3;
+    const int V = (nvec + S - 1) / S;
+    const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec), nv = vs1 - vs0;
+    constexpr int B = 4;
+    half8* xv = reinterpret_cast<half8*>(xs);
+    const half8* src = reinterpret_cast<const half8*>(r.src);
+    half8 zero;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) zero[c] = (half_t)0;
+
+    if (r.pro == AF_PRO_NONE) {
+      for (int i0 = tid; i0 < nv; i0 += B * THREADS) {
+        half8 t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) t[u] = (i0 + u * THREADS < nv) ? src[vs0 + i0 + u * THREADS] : zero;
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+          if (i0 + u * THREADS < nv) xv[i0 + u * THREADS] = t[u];
+      }
+    } else if (r.pro == AF_PRO_SILUMUL) {
+      const half8* up = reinterpret_cast<const half8*>(r.src + n);
+      for (int i0 = tid; i0 < nv; i0 += B * THREADS) {
+        half8 g[B], u8[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          const bool ok = i0 + u * THREADS < nv;
+          g[u] = ok ? src[vs0 + i0 + u * THREADS] : zero;
+          u8[u] = ok ? up[vs0 + i0 + u * THREADS] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          if (i0 + u * THREADS < nv) {
+            half8 h;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              const float gg = (float)g[u][c];
+              h[c] = (half_t)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * (float)u8[u][c]);
+            }
+            xv[i0 + u * THREADS] = h;
+          }
+        }
+      }
+    } else {  // AF_PRO_RMSNORM
+      const half8* gain = reinterpret_cast<const half8*>(r.gain);
+      // the range's own vectors (raw) and their gains travel with the first batch of the
+      // full pass, so there is one global round trip before the reduction
+      const bool single = nv <= B * THREADS;
+      half8 g[B];
+      if (single) {
+        half8 t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          const bool ok = tid + u * THREADS < nv;
+          t[u] = ok ? src[vs0 + tid + u * THREADS] : zero;
+          g[u] = ok ? gain[vs0 + tid + u * THREADS] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+          if (tid + u * THREADS < nv) xv[tid + u * THREADS] = t[u];
+      } else {
+        for (int i = tid; i < nv; i += THREADS) xv[i] = src[vs0 + i];
+      }
+      float ss = 0.f;
+      for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
+        half8 t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) ss += (float)t[u][c] * (float)t[u][c];
+        }
+      }
+      ss = af_wave_sum(ss);
+      if (lane == 0) sm.red[wave] = ss;
+      __syncthreads();
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) tot += sm.red[w];
+      const float scale = 1.0f / sqrtf(tot / (float)n + r.eps);
+      for (int i0 = tid; i0 < nv; i0 += B * THREADS) {
+        if (!single) {
+#pragma unroll
+          for (int u = 0; u < B; ++u) g[u] = (i0 + u * THREADS < nv) ? gain[vs0 + i0 + u * THREADS] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+          if (i0 + u * THREADS < nv) {
+            half8 h = xv[i0 + u * THREADS];   // each thread revisits the vectors it wrote
+#pragma unroll
+            for (int c = 0; c < 8; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
+            xv[i0 + u * THREADS] = h;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (store_x && r.x_out != nullptr) {
+      half8* dst = reinterpret_cast<half8*>(r.x_out);
+      for (int i = tid; i < nv; i += THREADS) dst[vs0 + i] = xv[i];
+    }
+
+    // count, scan, list: every thread owns a contiguous run of the range's vectors
+    const int T = threshold_key(r.t);
+    const int cv = (nv + THREADS - 1) / THREADS;
+    const int v0 = min(tid * cv, nv), v1 = min(v0 + cv, nv);
+    const u16x8* xb = reinterpret_cast<const u16x8*>(xs);
+    unsigned gt = 0;
+    for (int v = v0; v < v1; ++v) {
+      const u16x8 b = xb[v];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const unsigned key = b[c] & 0x7FFFu;
+        gt += ((int)key > T) & (key <= 0x7C00u);
+      }
+    }
+    unsigned tot;
+    unsigned pos = excl_scan(gt, sm, &tot);
+    if (gt != 0) {
+      for (int v = v0; v < v1; ++v) {
+        const u16x8 b = xb[v];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const unsigned bits = b[c];
+          const unsigned key = bits & 0x7FFFu;
+          if (((int)key > T) & (key <= 0x7C00u)) {
+            list[pos] = ((unsigned)((vs0 + v) * 8 + c) << 16) | bits;
+            ++pos;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    return (int)tot;
+  }
+
   // Select on xs[0..n) (n % 8 == 0) and keep the entries of split s of S in list[] as
   // (index << 16 | fp16 bits).  Returns the number of entries kept by this workgroup;
   // *nidx_total is the size of the whole index set.  `hist` is RP_SCRATCH_WORDS words of LDS.
@@ -214,13 +371,7 @@ struct RowPrologue {
     const bool topk = r.sel == AF_SEL_TOPK;
     if (!topk) {
       kmax = 0x7C00u;
-      if (r.t < 0.f) {
-        T = -1;
-      } else {
-        typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
-        const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(r.t, 0.f);  // toward zero = downward for t >= 0
-        T = (int)(__builtin_bit_cast(unsigned, h) & 0x7FFFu);
-      }
+      T = threshold_key(r.t);
     }
     if (topk && r.k > 0) {
       if (!hist_zeroed) {

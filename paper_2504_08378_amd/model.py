@@ -16,8 +16,9 @@ def layer_cfg(shape, weight_kind=B.AF_W_F16, rms_eps=1e-5, rope_theta=10000.0) -
                       rms_eps, rope_theta, weight_kind)
 
 
-def select_cfg(mode, k=(0, 0, 0, 0), t=(0.0, 0.0, 0.0, 0.0), reuse_mask=0) -> B.SelectCfg:
+def select_cfg(mode, k=(0, 0, 0, 0), t=(0.0, 0.0, 0.0, 0.0), reuse_mask=0, flags=0) -> B.SelectCfg:
     s = B.SelectCfg()
+    s.flags = flags
     s.mode = mode
     for p in range(4):
         s.k[p] = int(k[p])
@@ -133,7 +134,7 @@ class DeviceStack:
         self.ctx.decode_layer(self.cfg, self.layers[l].struct(), hidden_in, hidden_out, self.K[l],
                               self.V[l], kv_len, self.kv_cap, pos, sel, self.sets[l].struct())
 
-    def run(self, hidden_in, kv_len: int, pos: int, sel: B.SelectCfg, group: int = 1,
+    def run(self, hidden_in, kv_len: int, pos: int, sel, group: int = 1,
             reuse_points: int = 0, hidden_out=None):
         out = self.hidden_out if hidden_out is None else hidden_out
         self.ctx.decode_stack(self.cfg, self.w_array, self.n_layers, hidden_in, out, self.k_ptrs,

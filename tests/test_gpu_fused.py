@@ -117,3 +117,80 @@ def test_argument_errors(ctx):
         with pytest.raises(B.AfError) as e:
             ctx.select_gemv_f16(Wt, xd, **kw)
         assert e.value.status == code, kw
+
+
+# ---- threshold selection per channel range (no index list asked for) ---------------------
+def _run_noidx(ctx, Wt, src, n, **kw):
+    xo = torch.zeros(n, dtype=torch.float16, device="cuda")
+    y = ctx.select_gemv_f16(Wt, src, x_out=xo, sel_mode=B.AF_SEL_THRESHOLD, y_kind=B.AF_F32, **kw)
+    ctx.synchronize()
+    return to_host(y), to_host(xo)
+
+
+@pytest.mark.parametrize("out,n", [(136, 64), (520, 1000), (4096, 4096), (1032, 11008),
+                                   (2056, 5120), (264, 28672), (22016, 4096), (8, 32768)])
+def test_range_threshold_identity_producer(ctx, out, n):
+    W, x = _wx(out, n, out + n)
+    Wt = ctx.pack_inmajor_f16(to_dev(W)); xd = to_dev(x)
+    mags = np.sort(np.abs(x.astype(np.float64)))
+    for t in (-1.0, 0.0, float(mags[n // 2]), float(mags[(7 * n) // 10]), 1e9):
+        y, xo = _run_noidx(ctx, Wt, xd, n, t=t)
+        assert np.array_equal(xo.view(np.uint16), x.view(np.uint16))
+        ref_idx = O.select_threshold(x, t)
+        assert O.rel_err(y, O.sparse_gemv(W, x, ref_idx)) <= 1e-4, (t, len(ref_idx))
+
+
+def test_range_threshold_special_values_and_residual(ctx):
+    n, out = 2048, 520
+    W, x = _wx(out, n, 5)
+    z = x.copy(); z[7] = np.nan; z[9] = np.inf; z[11] = -np.inf; z[2040] = np.nan
+    W2 = W.copy(); W2[:, [9, 11]] = 0     # keep the reference finite: Inf channels meet zero weights
+    Wt = ctx.pack_inmajor_f16(to_dev(W2))
+    # NaN never passes; Inf passes any finite threshold (and multiplies a zero weight -> NaN in
+    # IEEE arithmetic, on both sides), so compare on a vector with the Infs removed as well
+    z2 = z.copy(); z2[[9, 11]] = 0
+    y, _ = _run_noidx(ctx, Wt, to_dev(z2), n, t=0.5)
+    ref_idx = O.select_threshold(z2, 0.5)
+    assert 7 not in ref_idx and 2040 not in ref_idx
+    # the oracle multiplies the masked vector out densely (NaN * 0 = NaN), so its input is the
+    # same vector with the unselected NaN channels cleared
+    z3 = z2.copy(); z3[[7, 2040]] = 0
+    assert O.rel_err(y, O.sparse_gemv(W2, z3, ref_idx)) <= 1e-4
+    res = S.activation(5, S.channel_scales(5, out, "r"), "r", 0)
+    y = ctx.select_gemv_f16(Wt, to_dev(x), sel_mode=B.AF_SEL_THRESHOLD, t=1e9, residual=to_dev(res))
+    ctx.synchronize()
+    assert np.array_equal(to_host(y), res)            # nothing passes: y is the residual
+
+
+@pytest.mark.parametrize("n,out", [(256, 264), (4096, 12288), (5120, 1032), (8192, 10240)])
+def test_range_threshold_rmsnorm_producer(ctx, n, out):
+    W, h = _wx(out, n, n + 1)
+    g = S.norm_gain(3, n, "fused")
+    x_ref = O.round_f16(O.rmsnorm(h, g, 1e-5))
+    t = float(np.sort(np.abs(x_ref.astype(np.float64)))[n // 2])
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    y, x_gpu = _run_noidx(ctx, Wt, to_dev(h), n, producer=B.AF_PRO_RMSNORM, gain=to_dev(g), eps=1e-5, t=t)
+    assert O.rel_err(x_gpu, x_ref) <= TOL
+    # same bits as the list-building form of the kernel
+    _, x_list, idx, c = _run(ctx, Wt, to_dev(h), n, producer=B.AF_PRO_RMSNORM, gain=to_dev(g),
+                             eps=1e-5, sel_mode=B.AF_SEL_THRESHOLD, t=t, y_kind=B.AF_F32)
+    assert np.array_equal(x_gpu.view(np.uint16), x_list.view(np.uint16))
+    # the GEMV, judged on the GPU's own x: the set follows from the definition
+    own = O.select_threshold(x_gpu, t)
+    assert np.array_equal(idx, own)
+    assert O.rel_err(y, O.sparse_gemv(W, x_gpu, own)) <= 1e-4
+    assert abs(len(own) / n - 0.5) < 0.02
+
+
+def test_range_threshold_silumul_producer(ctx):
+    n, out = 11008, 520
+    W, _ = _wx(out, n, 77)
+    sc = S.channel_scales(77, 2 * n, "gu")
+    gu = (S.activation(77, sc, "gu", 0).astype(np.float32) * 0.3).astype(np.float16)
+    x_ref = O.round_f16(O.silu(gu[:n]) * gu[n:].astype(np.float64))
+    t = float(np.sort(np.abs(x_ref.astype(np.float64)))[n // 2])
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    y, x_gpu = _run_noidx(ctx, Wt, to_dev(gu), n, producer=B.AF_PRO_SILUMUL, t=t)
+    assert O.rel_err(x_gpu, x_ref) <= TOL
+    own = O.select_threshold(x_gpu, t)
+    assert O.rel_err(y, O.sparse_gemv(W, x_gpu, own)) <= 1e-4

@@ -356,3 +356,106 @@ def test_13b_shape_reuse_pair(ctx):
             cos = got_h @ ref_h / np.linalg.norm(got_h) / np.linalg.norm(ref_h)
             assert cos > 0.9995, (sp, cos)
         print(f"13b sp={sp}: oracle overlap of the follower {ov[1]}, leader sets identical: {same}")
+
+
+# ---- threshold form without index sets (AF_SEL_SKIP_SETS), per-layer thresholds ----------
+def _gap_thresholds(xs):
+    """One threshold per point, in the widest gap of the middle third of its magnitudes."""
+    ts = []
+    for x in xs:
+        m = np.sort(np.abs(np.asarray(x).astype(np.float64)))
+        gaps = np.diff(m)
+        lo = len(m) // 3
+        j = lo + int(np.argmax(gaps[lo: 2 * len(m) // 3]))
+        ts.append(float(np.float32((m[j] + m[j + 1]) / 2)))
+    return tuple(ts)
+
+
+def _keeps_match(x_gpu, t, ref_idx):
+    """The set the definition gives on the GPU's own vector equals the oracle's set."""
+    return np.array_equal(O.select_threshold(x_gpu, t), ref_idx)
+
+
+@pytest.mark.parametrize("kind", [B.AF_W_F16, B.AF_W_Q4G32])
+def test_layer_threshold_without_sets(ctx, kind):
+    shape = S.MODEL_SHAPES["tiny_gqa"]
+    layers, kv, h = _host_stack(shape, 1, seed=8)
+    q4 = kind == B.AF_W_Q4G32
+    w0 = {k: (O.quantize_q4_g32(v) if (q4 and k.startswith("W")) else v) for k, v in layers[0].items()}
+    run_o = lambda sel: O.decode_layer(_ocfg(shape), w0, h, kv[0][0].copy(), kv[0][1].copy(), KV_LEN,
+                                       KV_LEN, sel, weights_q4=q4)
+    ts = _gap_thresholds(run_o(O.SelectCfg(O.SEL_TOPK, _ks(shape, 50))).x)
+    tr = run_o(O.SelectCfg(O.SEL_THRESHOLD, t=ts))
+    st = _dev_stack(ctx, shape, layers, kv, kind=kind)
+    for p in range(4):
+        st.sets[0].idx[p].fill_(-7); st.sets[0].count[p].fill_(-7)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    st.layer(0, hin, hout, KV_LEN, KV_LEN, M.select_cfg(B.AF_SEL_THRESHOLD, t=ts, flags=B.AF_SEL_SKIP_SETS))
+    ctx.synchronize()
+    for p in range(4):   # nothing was written
+        assert int(st.sets[0].count[p].item()) == -7 and int(st.sets[0].idx[p].min().item()) == -7
+    t = _taps(ctx, shape)
+    xs = (t["x_qkv"], t["attn"], t["x_gateup"], t["x_down"])
+    same = all(_keeps_match(xs[p], ts[p], tr.idx[p]) for p in range(4))
+    for p, name in enumerate(("x_qkv", "attn", "x_gateup", "x_down")):
+        assert O.rel_err(xs[p], tr.x[p], 1.0) <= (TOL if same else 5e-2), name
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
+    # identical bits to the list-building form on the same inputs
+    hout2 = torch.zeros_like(hin)
+    st.layer(0, hin, hout2, KV_LEN, KV_LEN, M.select_cfg(B.AF_SEL_THRESHOLD, t=ts))
+    ctx.synchronize()
+    for p in range(4):
+        assert np.array_equal(st.sets[0].fetch(p), O.select_threshold(xs[p], ts[p])) or not same
+    assert O.rel_err(to_host(hout2), to_host(hout), 1.0) <= 1e-3
+    # sets may be absent altogether
+    ctx.decode_layer(st.cfg, st.layers[0].struct(), hin, hout2, st.K[0], st.V[0], KV_LEN, KV_CAP, KV_LEN,
+                     M.select_cfg(B.AF_SEL_THRESHOLD, t=ts, flags=B.AF_SEL_SKIP_SETS), B.IdxSets())
+    ctx.synchronize()
+    assert np.array_equal(to_host(hout2), to_host(hout))
+
+
+def test_stack_per_layer_thresholds_skip_sets_and_reuse(ctx):
+    """Four layers, every layer with its own thresholds; groups of two: the leaders write the
+    sets their followers read, nobody else writes any."""
+    shape = S.MODEL_SHAPES["tiny_gqa"]
+    L = 4
+    layers, kv, h = _host_stack(shape, L, seed=9)
+    ocfg = _ocfg(shape)
+    # Thresholds layer by layer, point by point, along the threshold-mode chain itself: the
+    # input of point p depends on the thresholds of the points before it, so each is placed
+    # in a gap of the magnitudes the earlier choices lead to.  Both sides then keep the same
+    # channels as long as their inputs agree to well within the gap.
+    sels_o, hcur = [], h
+    for l in range(L):
+        ts = [0.0, 0.0, 0.0, 0.0]
+        for p in range(4):
+            tr = O.decode_layer(ocfg, layers[l], hcur, kv[l][0].copy(), kv[l][1].copy(), KV_LEN, KV_LEN,
+                                O.SelectCfg(O.SEL_THRESHOLD, t=tuple(ts)))
+            ts[p] = _gap_thresholds([tr.x[p]])[0]
+        sels_o.append(O.SelectCfg(O.SEL_THRESHOLD, t=tuple(ts)))
+        hcur = O.decode_layer(ocfg, layers[l], hcur, kv[l][0].copy(), kv[l][1].copy(), KV_LEN, KV_LEN,
+                              sels_o[-1]).hidden
+    for group, points in ((1, 0), (2, 0b1111), (2, 0b0101)):
+        Ks = [k.copy() for k, _ in kv]; Vs = [v.copy() for _, v in kv]
+        traces, _ = O.decode_stack(ocfg, layers, h, Ks, Vs, KV_LEN, KV_LEN, sels_o, group=group,
+                                   reuse_points=points)
+        st = _dev_stack(ctx, shape, layers, kv)
+        for l in range(L):
+            for p in range(4):
+                st.sets[l].idx[p].fill_(-7); st.sets[l].count[p].fill_(-7)
+        sels = [M.select_cfg(B.AF_SEL_THRESHOLD, t=s.t, flags=B.AF_SEL_SKIP_SETS) for s in sels_o]
+        out = st.run(to_dev(h), KV_LEN, KV_LEN, sels, group=group, reuse_points=points)
+        ctx.synchronize()
+        same = True
+        for l in range(L):
+            leader = group > 1 and l % group == 0
+            for p in range(4):
+                written = int(st.sets[l].count[p].item()) != -7
+                assert written == (leader and bool(points >> p & 1)), (group, l, p)
+                if written:
+                    same &= np.array_equal(st.sets[l].fetch(p), traces[l].idx[p])
+        err = O.rel_err(to_host(out), traces[-1].hidden, 1.0)
+        assert err <= (2 * TOL if same else 5e-2), (group, points, err)
+    # a wrong number of configurations is refused
+    with pytest.raises(B.AfError):
+        st.run(to_dev(h), KV_LEN, KV_LEN, sels[:3])
