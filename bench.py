@@ -127,6 +127,10 @@ def main() -> int:
     ap.add_argument("--weights", default="f16", choices=["f16", "q4"])
     ap.add_argument("--group", type=int, default=1, help="cross-layer reuse group (1 = none)")
     ap.add_argument("--reuse-points", type=lambda s: int(s, 0), default=0b1111)
+    ap.add_argument("--select", default="topk", choices=["topk", "threshold"],
+                    help="threshold: per-operator thresholds calibrated for --sparsity on "
+                         "--calib-tokens synthetic tokens, selection fused into the GEMVs")
+    ap.add_argument("--calib-tokens", type=int, default=8)
     ap.add_argument("--kv-len", type=int, default=512)
     ap.add_argument("--overlap", action="store_true",
                     help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
@@ -156,6 +160,9 @@ def main() -> int:
 
     if args.union:
         return union_bench(args, S, B, torch, np)
+    if args.overlap and args.select != "topk":
+        print("bench.py: --overlap compares top-k sets; use it with --select topk", file=sys.stderr)
+        return 2
 
     base = S.MODEL_SHAPES[args.shape]
     L = args.layers or base.n_layers
@@ -191,6 +198,34 @@ def main() -> int:
         del ca, cb
 
     sel = M.select_cfg(B.AF_SEL_TOPK, ks)
+    keep_frac = None
+    if args.select == "threshold":
+        # Calibration (untimed): decode --calib-tokens synthetic tokens layer by layer with
+        # top-k selection at the target sparsity, pooling the magnitudes of every operator's
+        # input; the thresholds of one operator come from its pooled histogram.
+        hists = [[ctx.calib_hist() for _ in range(4)] for _ in range(L)]
+        torch.cuda.synchronize()
+        scales = S.channel_scales(0, shape.d_model, shape.name)
+        bufs = [torch.zeros_like(hin), torch.zeros_like(hin)]
+        for tok in range(1, args.calib_tokens + 1):
+            cur = torch.from_numpy(S.activation(0, scales, "hidden", tok)).cuda()
+            torch.cuda.synchronize()
+            for l in range(L):
+                st.layer(l, cur, bufs[l & 1], kv_len, kv_len, sel)
+                ctx.calib_accumulate_layer(st.cfg, hists[l])
+                cur = bufs[l & 1]
+            ctx.synchronize()
+        t_dev = [[ctx.calib_thresholds(hists[l][p], [sp]) for p in range(4)] for l in range(L)]
+        ctx.synchronize()            # the library's stream, not torch's: .item() would not wait for it
+        thr = [[float(t_dev[l][p].item()) for p in range(4)] for l in range(L)]
+        # kept fraction on the bench token (eager, sets written), then the timed configuration
+        sel_sets = [M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l]) for l in range(L)]
+        st.run(hin, kv_len, kv_len, sel_sets, group=args.group, reuse_points=args.reuse_points)
+        ctx.synchronize()
+        src_of = lambda l, p: l - l % args.group if (args.group > 1 and args.reuse_points >> p & 1) else l
+        kept = [[int(st.sets[src_of(l, p)].count[p].item()) for p in range(4)] for l in range(L)]
+        keep_frac = [round(sum(kept[l][p] for l in range(L)) / (L * widths[p]), 4) for p in range(4)]
+        sel = [M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l], flags=B.AF_SEL_SKIP_SETS) for l in range(L)]
     run = lambda: st.run(hin, kv_len, kv_len, sel, group=args.group, reuse_points=args.reuse_points)
     run()
     ctx.synchronize()
@@ -218,12 +253,11 @@ def main() -> int:
 
     # active weight bytes of one token (the four operators of every layer)
     bpw = 2.0 if kind == B.AF_W_F16 else 0.5
-    per_layer = (ks[0] * shape.qkv_out + ks[1] * shape.d_model + ks[2] * 2 * shape.d_ffn
-                 + ks[3] * shape.d_model) * bpw
+    outs = (shape.qkv_out, shape.d_model, 2 * shape.d_ffn, shape.d_model)
+    rows = [list(ks)] * L if keep_frac is None else kept     # active channels per layer and point
+    active_bytes = sum(rows[l][p] * outs[p] for l in range(L) for p in range(4)) * bpw
     if kind == B.AF_W_Q4G32:   # every scale row is touched at these sparsities
-        per_layer += (shape.d_model // 32 * shape.qkv_out + widths[1] // 32 * shape.d_model
-                      + shape.d_model // 32 * 2 * shape.d_ffn + shape.d_ffn // 32 * shape.d_model) * 2
-    active_bytes = per_layer * L
+        active_bytes += L * sum(widths[p] // 32 * outs[p] for p in range(4)) * 2
 
     # ---- roofline of the dominant kernel ------------------------------------------------
     # The gate|up operator as it runs inside the step: one launch that builds
@@ -239,13 +273,31 @@ def main() -> int:
 
     def gateup(l):
         lay = st.layers[l]
-        if kind == B.AF_W_F16:
+        if kind == B.AF_W_F16 and keep_frac is not None:
+            ctx.select_gemv_f16(lay.Wgateup, h2, producer=B.AF_PRO_RMSNORM, gain=lay.g_ffn, eps=1e-5,
+                                sel_mode=B.AF_SEL_THRESHOLD, t=t2, x_out=x2, y=y2)
+        elif kind == B.AF_W_F16:
             ctx.select_gemv_f16(lay.Wgateup, h2, producer=B.AF_PRO_RMSNORM, gain=lay.g_ffn, eps=1e-5,
                                 sel_mode=B.AF_SEL_TOPK, k=ks[2], x_out=x2, idx_out=idx2,
                                 count_out=cnt2, y=y2)
         else:
             ctx.sparse_gemv_q4(lay.Wgateup, lay.Sgateup, h2, st.sets[0].idx[2], nidx=ks[2], y=y2)
 
+    rows2 = ks[2]
+    if keep_frac is not None and kind == B.AF_W_F16:
+        # the roofline vector is not a hidden state of the stack: give it its own threshold,
+        # and count the rows that threshold really keeps
+        hx = ctx.calib_hist()
+        torch.cuda.synchronize()
+        ctx.select_gemv_f16(st.layers[0].Wgateup, h2, producer=B.AF_PRO_RMSNORM, gain=st.layers[0].g_ffn,
+                            eps=1e-5, sel_mode=B.AF_SEL_DENSE, x_out=x2, y=y2)
+        ctx.calib_accumulate(x2, hx)
+        t2_dev = ctx.calib_thresholds(hx, [sp])
+        ctx.synchronize()
+        t2 = float(t2_dev.item())
+        _, c2 = ctx.select_threshold(x2, t2)
+        ctx.synchronize()
+        rows2 = int(c2.item())
     reps = max(1, 256 // L)
     for l in range(L):
         gateup(l)
@@ -261,8 +313,11 @@ def main() -> int:
     us_per_launch = e0.elapsed_time(e1) * 1e3 / launches
     if kind == B.AF_W_F16:
         # k rows of weights with their (x, idx) pairs, the result, plus the norm's input and gain
-        alg = gemv_bytes(ks[2], 2 * shape.d_ffn) + 2 * shape.d_model * 2
+        alg = gemv_bytes(rows2, 2 * shape.d_ffn) + 2 * shape.d_model * 2
         kname = "gemv_f16_kernel<32, 8, 16> (gate|up: rmsnorm + top-k + gathered GEMV)"
+        if keep_frac is not None:
+            alg -= rows2 * 4     # no index list travels through memory
+            kname = "gemv_f16_kernel (gate|up: rmsnorm + per-range threshold + gathered GEMV)"
     else:
         alg = ks[2] * (shape.d_ffn + 6) + (shape.d_model // 32) * 2 * shape.d_ffn * 2 + 2 * shape.d_ffn * 2
         kname = "gemv_q4_kernel (gate|up)"
@@ -270,7 +325,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": kname,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.shape, args.weights, sp)) if L == base.n_layers and args.group == 1 else None,
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.shape, args.weights, sp))
+                if L == base.n_layers and args.group == 1 and keep_frac is None else None,
                 "bytes_per_launch": alg, "us_per_launch": round(us_per_launch, 3), "launches": launches}
 
     # ---- the box's plain streaming-read rate (what an ideal reader of these bytes gets) ----
@@ -306,10 +362,11 @@ def main() -> int:
             wq = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in host_layer0.items()}
         n_done, t_cpu, h = 0, 0.0, h_host
         tr = None
+        osel = O.SelectCfg(O.SEL_TOPK, ks) if keep_frac is None else O.SelectCfg(O.SEL_THRESHOLD, t=tuple(thr[0]))
         while n_done < 40 and t_cpu < 12.0:
             t1 = time.perf_counter()
             tr = O.decode_layer(ocfg, wq, h, K0.copy(), V0.copy(), kv_len, kv_len,
-                                O.SelectCfg(O.SEL_TOPK, ks), weights_q4=(kind == B.AF_W_Q4G32))
+                                osel, weights_q4=(kind == B.AF_W_Q4G32))
             t_cpu += time.perf_counter() - t1
             n_done += 1
             if n_done == 1:
@@ -319,13 +376,15 @@ def main() -> int:
                "sample": f"layer 0 of the stack decoded {n_done}x by the fp64 NumPy oracle "
                          f"({t_cpu:.1f} s), scaled to {L} layers"}
         # correctness of the timed buffers: layer 0 of the GPU stack against the oracle
-        st.layer(0, hin, st.hidden_out, kv_len, kv_len, sel)
+        sel0 = M.select_cfg(B.AF_SEL_TOPK, ks) if keep_frac is None else M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[0])
+        st.layer(0, hin, st.hidden_out, kv_len, kv_len, sel0)
         ctx.synchronize()
-        got0 = st.sets[0].fetch(0, ks[0])
+        got0 = st.sets[0].fetch(0, len(first.idx[0]))
         if not np.array_equal(got0, first.idx[0]):
             print("bench.py: WARNING layer-0 qkv index set differs from the oracle", file=sys.stderr)
         st.sets[0].load(first.idx)
-        st.layer(0, hin, st.hidden_out, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+        sel0.reuse_mask = 0b1111
+        st.layer(0, hin, st.hidden_out, kv_len, kv_len, sel0)
         ctx.synchronize()
         err = O.rel_err(st.hidden_out.cpu().numpy(), first.hidden, 1.0)   # chained stages: rms floor
         cpu["gpu_vs_oracle_rel_err_layer0"] = float(f"{err:.3e}")
@@ -373,6 +432,8 @@ def main() -> int:
 
     wl = f"{args.shape}-shape decoder stack, {L} layers, batch-1 decode, {args.weights} weights, " \
          f"{sp}% sparsity at qkv/o/gate-up/down, {kv_len}-token KV cache"
+    if keep_frac is not None:
+        wl += f", threshold selection calibrated on {args.calib_tokens} tokens (no index lists)"
     if args.group > 1:
         wl += f", index reuse in groups of {args.group} (points mask {args.reuse_points:#06b})"
     out = {
@@ -390,6 +451,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if keep_frac is not None:
+        out["config"]["kept_fraction_by_point"] = keep_frac
     if overlap is not None:
         out["overlap_reused_vs_own"] = overlap
     print(json.dumps(out))

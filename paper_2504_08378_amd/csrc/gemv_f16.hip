@@ -105,12 +105,29 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
         for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv;
       }
     }
-    for (; i < cnt; i += STEP) {
-      const unsigned e = s_list[i];
-      const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu));
-      const half8 w = *reinterpret_cast<const half8*>(wcol + (size_t)(e >> 16) * p.ld);
+    // Ragged end: one more batch of the same depth with the missing rows masked off, so its
+    // loads are all in flight together (a row-at-a-time loop would pay one memory round trip
+    // per row, up to U - 1 of them in a row).
+    if (i < cnt) {
+      half8 w[U];
+      unsigned e[U];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[c] += (float)w[c] * xv;
+      for (int u = 0; u < U; ++u) {
+        const bool ok = i + u * STEP < cnt;
+        e[u] = ok ? s_list[i + u * STEP] : 0u;
+        if (ok) {
+          w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
+        } else {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) w[u][c] = (half_t)0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e[u] & 0xFFFFu));
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv;
+      }
     }
   };
 

@@ -127,10 +127,19 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
 #pragma unroll
       for (int u = 0; u < U; ++u) consume(e[u], w[u]);
     }
-    for (; i < iend; ++i) {
-      const unsigned e = s_list[i];
-      const unsigned w = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e >> 16) * row_bytes);
-      consume(e, w);
+    // Ragged end: one more batch of the same depth with the missing rows masked off, so its
+    // loads are in flight together instead of one memory round trip per row.
+    if (i < iend) {
+      unsigned w[U], e[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool ok = i + u < iend;
+        e[u] = ok ? s_list[i + u] : 0u;
+        w[u] = ok ? *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (i + u < iend) consume(e[u], w[u]);
     }
   };
 

@@ -134,14 +134,29 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
         }
       }
     }
-    for (; i < cnt; i += STEP) {
-      const half8 w = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i] * p.ld);
-      const half8 xm = s_xm[i];
+    // ragged end: one masked batch of the same depth, its loads in flight together
+    if (i < cnt) {
+      half8 w[U];
 #pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        const float xv = (float)xm[b];
+      for (int u = 0; u < U; ++u) {
+        if (i + u * STEP < cnt) {
+          w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld);
+        } else {
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[b][c] += (float)w[c] * xv;
+          for (int c = 0; c < 8; ++c) w[u][c] = (half_t)0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (i + u * STEP < cnt) {
+          const half8 xm = s_xm[i + u * STEP];
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const float xv = (float)xm[b];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[b][c] += (float)w[u][c] * xv;
+          }
+        }
       }
     }
   }
