@@ -69,6 +69,40 @@ struct af_row_src {
   int32_t* count_out;
 };
 
+// Dynamic LDS of a fused GEMV workgroup: [x as fp16 | staged rows as uint32].  A workgroup that
+// selects keeps its whole share of the rows staged, so the share has to fit: *S (the number
+// of row splits) is raised until it does.  Rows given by the caller are staged `chunk` at a
+// time instead.  Returns false if nothing fits.
+#define AF_GEMV_LDS_BUDGET (120u * 1024u)  // leaves room for the kernels' static LDS in 160 KB
+static inline bool af_plan_gemv_lds(const af_row_src& r, int max_rows, bool use_lds_x,
+                                    bool range_sel, int chunk, int* S, size_t* xs_bytes,
+                                    int* list_cap) {
+  for (int s = *S < 1 ? 1 : *S; s <= 4096; ++s) {
+    size_t xb;
+    int cap;
+    if (range_sel) {
+      cap = 8 * ((r.n / 8 + s - 1) / s);  // a channel range, whole 8-element vectors
+      xb = (size_t)cap * 2;
+    } else if (r.sel != AF_ROWS_GIVEN) {
+      cap = (max_rows + s - 1) / s;
+      xb = (size_t)r.n * 2;
+    } else {
+      cap = chunk;
+      xb = use_lds_x ? (size_t)r.n * 2 : 0;
+    }
+    xb = (xb + 15) / 16 * 16;
+    if (cap < 64) cap = 64;
+    if (xb + (size_t)cap * 4 <= AF_GEMV_LDS_BUDGET) {
+      *S = s;
+      *xs_bytes = xb;
+      *list_cap = cap;
+      return true;
+    }
+    if (r.sel == AF_ROWS_GIVEN) return false;
+  }
+  return false;
+}
+
 struct af_gemv_args {
   const void* W;          // fp16 in-major, or packed nibbles
   const half_t* scales;   // q4 only

@@ -19,7 +19,7 @@
 #include "af_internal.h"
 #include "row_prologue.h"
 
-#define GEMV_LIST 2048  // staged rows per pass: (index << 16 | fp16 bits of x)
+#define GEMV_LIST 2048  // rows given by the caller are staged this many at a time
 
 struct GemvParams {
   const half_t* W;
@@ -30,6 +30,7 @@ struct GemvParams {
   const half_t* residual;
   int out, ld, y_kind, out_pad, use_lds_x;
   int range_sel;  // threshold selection per channel range, no list for the whole vector
+  int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
@@ -51,10 +52,11 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   typedef RowPrologue<GEMV_THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];  // the operator input, when built here
   __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
-  __shared__ unsigned s_list[GEMV_LIST];
   __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
   float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
+  // staged rows, (index << 16 | fp16 bits of x)
+  unsigned* s_list = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(xs) + p.list_off);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
@@ -221,11 +223,14 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
 // AF_GEMV_SPLIT / AF_GEMV_WGS in the environment override the heuristic (tuning sweeps).
 static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, int* lx_out,
                           int* nw_out, int* s_out) {
-  // Measured on the 7B operators (cold matrices): 128-column tiles (256 B per row and
-  // workgroup) win up to ~16K columns, 256-column tiles beyond.  A kernel that selects for
+  // Measured on the 7B and 13B operators (cold matrices): 128-column tiles (256 B per row and
+  // workgroup) win up to ~16K columns, 512-column tiles (1 KB) beyond.  With 256-column tiles
+  // on a row stride that is a multiple of 1 KB every workgroup stays on one value of address
+  // bit 9 for all its rows, and the half of the workgroups on one of the two values finished
+  // ~2 us after the other half.  A kernel that selects for
   // itself (or builds its input vector) repeats that work in every workgroup, so it runs few, large workgroups
   // (one per CU); a plain GEMV prefers several small ones per CU.
-  int lx = out <= 16384 ? 16 : 32;
+  int lx = out <= 16384 ? 16 : 64;
   int nw = selects ? 16 : 4;
   if (const char* e = getenv("AF_GEMV_LX")) {
     int v = atoi(e);
@@ -261,10 +266,10 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
 template <int LX, int NW>
 static void launch_one(dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
   static bool attr_done = false;
-  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
+  if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
   hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
@@ -290,16 +295,15 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   const int tiles = (a.out + tw - 1) / tw;
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
-  // a selecting workgroup keeps its whole split in the staged list
   const bool range_sel = r.sel == AF_SEL_THRESHOLD && !r.idx_out && !r.count_out;
-  auto split_fits = [&](int s_try) {
-    if (r.sel == AF_ROWS_GIVEN) return true;
-    if (range_sel) return 8 * ((r.n / 8 + s_try - 1) / s_try) <= GEMV_LIST;
-    return (size_t)s_try * GEMV_LIST >= (size_t)max_rows;
-  };
-  while (!split_fits(S)) ++S;
+  const bool use_lds_x = r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN;
+  size_t xs_bytes;
+  int list_cap;
+  // the split partial sums have to fit the workspace, the staged rows of a split the LDS
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (!split_fits(S)) return AF_EWORKSPACE;
+  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, GEMV_LIST, &S, &xs_bytes, &list_cap))
+    return AF_EWORKSPACE;
+  if (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) return AF_EWORKSPACE;
   GemvParams p;
   p.W = (const half_t*)a.W;
   p.rows = r;
@@ -311,9 +315,10 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.ld = a.ld;
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
-  p.use_lds_x = (r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN) ? 1 : 0;
+  p.use_lds_x = use_lds_x ? 1 : 0;
   p.range_sel = range_sel ? 1 : 0;
-  const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
+  p.list_off = (int)xs_bytes;
+  const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)
     launch_lx<64>(nw, grid, lds, ctx->stream, p);

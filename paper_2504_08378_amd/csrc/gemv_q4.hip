@@ -17,7 +17,7 @@
 #include "af_internal.h"
 #include "row_prologue.h"
 
-#define Q4_LIST 2048  // staged rows per pass: (index << 16 | fp16 bits of x)
+#define Q4_LIST 2048  // rows given by the caller are staged this many at a time
 
 struct Q4Params {
   const unsigned char* packed;
@@ -29,6 +29,7 @@ struct Q4Params {
   const half_t* residual;
   int out, ld, y_kind, out_pad, use_lds_x;
   int range_sel;  // threshold selection per channel range, no list for the whole vector
+  int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
@@ -70,10 +71,11 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   typedef RowPrologue<THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];
   __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
-  __shared__ unsigned s_list[Q4_LIST];
   __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
   float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
+  // staged rows, (index << 16 | fp16 bits of x)
+  unsigned* s_list = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(xs) + p.list_off);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
@@ -220,10 +222,10 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
 template <int LX, int NW>
 static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   static bool attr_done = false;
-  if (!attr_done) {  // the input vector can need up to 64 KB of dynamic LDS
+  if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
   hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
@@ -269,14 +271,14 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   if (S > 256) S = 256;
   if (S < 1) S = 1;
   const bool range_sel = r.sel == AF_SEL_THRESHOLD && !r.idx_out && !r.count_out;
-  auto split_fits = [&](int s_try) {  // a selecting workgroup keeps its whole split in the list
-    if (!selects) return true;
-    if (range_sel) return 8 * ((r.n / 8 + s_try - 1) / s_try) <= Q4_LIST;
-    return (size_t)s_try * Q4_LIST >= (size_t)max_rows;
-  };
-  while (!split_fits(S)) ++S;
+  const bool use_lds_x = r.pro != AF_PRO_NONE || selects;
+  size_t xs_bytes;
+  int list_cap;
+  // the split partial sums have to fit the workspace, the staged rows of a split the LDS
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (!split_fits(S)) return AF_EWORKSPACE;
+  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, Q4_LIST, &S, &xs_bytes, &list_cap))
+    return AF_EWORKSPACE;
+  if (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) return AF_EWORKSPACE;
   Q4Params p;
   p.packed = (const unsigned char*)a.W;
   p.scales = a.scales;
@@ -289,9 +291,10 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   p.ld = a.ld;
   p.y_kind = a.y_kind;
   p.out_pad = out_pad;
-  p.use_lds_x = (r.pro != AF_PRO_NONE || selects) ? 1 : 0;
+  p.use_lds_x = use_lds_x ? 1 : 0;
   p.range_sel = range_sel ? 1 : 0;
-  const size_t lds = p.use_lds_x ? af_align((size_t)r.n * 2, 16) : 0;
+  p.list_off = (int)xs_bytes;
+  const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)
     q4_launch_lx<64>(nw, grid, lds, ctx->stream, p);
