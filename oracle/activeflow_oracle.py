@@ -20,7 +20,8 @@ What it follows (ActiveFlow, arXiv 2504.08378):
     of the next layers of its group (N = 4) -> decode_stack(reuse...), overlap.
   * Section 6 ("Flash loading") and Section 7.1: weights are 4-bit with the
     matrix transposed so that a channel read carries its scales -> the q4
-    functions (the quantiser itself is this build's own definition, see below).
+    functions (the quantiser itself is this build's own definition, see below);
+    quantize_q4_cl is the arrangement with the groups inside a channel's row.
   * Fig. "simplified transformer layer" (Section 2.2): pre-norm block with
     residual connections -> decode_layer.
   * Eq. 9: sparsity sp is the fraction of channels dropped -> keep_count.
@@ -181,6 +182,39 @@ def sparse_gemv_q4(nib, scales, x, idx) -> np.ndarray:
     return sparse_gemv(dequant_q4_g32(nib, scales), x, idx)
 
 
+def quantize_q4_cl(W):
+    """Channel-local variant: the groups lie inside one input channel's row of the
+    transposed matrix (Section 6 "Flash loading": the transpose lets a channel read bring
+    all the scales it needs), 32 consecutive output columns per group.  Same scale and
+    rounding rules as quantize_q4_g32.  W[out][in] fp16 -> (nib uint8 [out][in],
+    scales fp16 [in][out/32])."""
+    W = np.asarray(W, dtype=np.float16)
+    out, n_in = W.shape
+    if out % Q4_GROUP:
+        raise ValueError("out must be a multiple of 32")
+    w32 = W.astype(np.float32).T.reshape(n_in, out // Q4_GROUP, Q4_GROUP)   # [in][group][32]
+    amax = np.max(np.abs(w32), axis=2)
+    s16 = (amax / np.float32(7.0)).astype(np.float32).astype(np.float16)
+    s32 = s16.astype(np.float32)[:, :, None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.rint((w32 / s32).astype(np.float32))
+    q = np.where(s32 == 0, np.float32(0), np.clip(r, -7, 7)).astype(np.int32)
+    nib = (q + 8).astype(np.uint8).reshape(n_in, out).T
+    return np.ascontiguousarray(nib), np.ascontiguousarray(s16)
+
+
+def dequant_q4_cl(nib, scales) -> np.ndarray:
+    """(nib - 8) * scale of (input channel, group of 32 output columns), fp64 [out][in]."""
+    nib = np.asarray(nib)
+    s = np.asarray(scales).astype(np.float64)          # [in][out/32]
+    q = nib.astype(np.float64) - 8.0
+    return q * np.repeat(s, Q4_GROUP, axis=1).T
+
+
+def sparse_gemv_q4_cl(nib, scales, x, idx) -> np.ndarray:
+    return sparse_gemv(dequant_q4_cl(nib, scales), x, idx)
+
+
 # --------------------------------------------------------------------------
 # small-batch union (each token keeps its own mask)
 # --------------------------------------------------------------------------
@@ -298,6 +332,11 @@ def _select(x16, p: int, sel: SelectCfg, given):
 
 
 def _linear(W, x16, idx, weights_q4):
+    """weights_q4: False (fp16 matrix), True (group-32-along-input pair) or "cl"
+    (channel-local pair)."""
+    if weights_q4 == "cl":
+        nib, s = W
+        return sparse_gemv_q4_cl(nib, s, x16, idx)
     if weights_q4:
         nib, s = W
         return sparse_gemv_q4(nib, s, x16, idx)

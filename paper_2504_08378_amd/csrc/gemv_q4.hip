@@ -219,15 +219,18 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
+#ifndef Q4_U
+#define Q4_U 8
+#endif
 template <int LX, int NW>
 static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, Q4_U, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_q4_kernel<LX, Q4_U, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
 
 template <int LX>

@@ -159,6 +159,52 @@ def test_q4_gemv_against_scalar_loop():
     assert np.allclose(O.sparse_gemv_q4(nib, s, x, idx), exp, rtol=1e-12, atol=1e-18)
 
 
+# ------------------------------------------------- 4-bit, channel-local groups
+def test_q4_cl_golden_group():
+    """The hand-worked group of the fixture, laid along the output dim of one input channel."""
+    rows = [l for l in open(os.path.join(GOLDEN, "q4_worked.txt")) if l.strip() and not l.startswith("#")]
+    w64 = np.array([float(v) for v in rows[0].split()])
+    q_exp = np.array([int(v) for v in rows[1].split()])
+    W = (w64 / 64.0).astype(np.float16).reshape(32, 1)                   # [out = 32][in = 1]
+    nib, s = O.quantize_q4_cl(W)
+    assert s.shape == (1, 1) and float(s[0, 0]) == 1.0 / 64.0
+    assert np.array_equal(nib[:, 0].astype(int) - 8, q_exp)
+    assert np.array_equal(O.dequant_q4_cl(nib, s)[:, 0], q_exp / 64.0)
+
+
+def test_q4_cl_is_g32_of_the_transpose():
+    """Grouping 32 output columns of channel j is grouping 32 'input channels' of the
+    transposed matrix: the two quantisers must agree through that relabelling."""
+    g = np.random.default_rng(15)
+    out, n = 64, 24
+    W = (g.standard_normal((out, n)) * 0.02).astype(np.float16)
+    nib_cl, s_cl = O.quantize_q4_cl(W)
+    nib_t, s_t = O.quantize_q4_g32(np.ascontiguousarray(W.T))           # [in][out] as if out-major
+    assert np.array_equal(nib_cl, nib_t.T)
+    assert np.array_equal(s_cl, s_t.T)                                   # [in][out/32] vs [out/32][in]
+    assert np.array_equal(O.dequant_q4_cl(nib_cl, s_cl), O.dequant_q4_g32(nib_t, s_t).T)
+
+
+def test_q4_cl_error_bound_and_gemv_scalar_loop():
+    g = np.random.default_rng(16)
+    out, n = 96, 40
+    W = (g.standard_normal((out, n)) * 0.02).astype(np.float16)
+    nib, s = O.quantize_q4_cl(W)
+    assert nib.min() >= 1 and nib.max() <= 15 and s.shape == (n, out // 32) and s.dtype == np.float16
+    deq = O.dequant_q4_cl(nib, s)
+    sfull = np.repeat(s.astype(np.float64), 32, axis=1).T
+    assert np.all(np.abs(W.astype(np.float64) - deq) <= 0.5 * sfull * (1 + 1e-6) + 7 * sfull * 2.0 ** -11)
+    x = g.laplace(size=n).astype(np.float16)
+    idx = np.sort(g.choice(n, size=17, replace=False)).astype(np.int32)
+    exp = [math.fsum((int(nib[o, j]) - 8) * float(s[j, o // 32]) * float(x[j]) for j in idx) for o in range(out)]
+    assert np.allclose(O.sparse_gemv_q4_cl(nib, s, x, idx), exp, rtol=1e-12, atol=1e-18)
+    # a channel's scales depend on that channel alone (what makes its bytes self-contained)
+    W2 = W.copy(); W2[:, 5] *= np.float16(3.0)
+    nib2, s2 = O.quantize_q4_cl(W2)
+    keep = np.arange(n) != 5
+    assert np.array_equal(s2[keep], s[keep]) and np.array_equal(nib2[:, keep], nib[:, keep])
+
+
 # ----------------------------------------------------------------------- union
 def test_union_small_batch():
     g = np.random.default_rng(8)
