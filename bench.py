@@ -124,7 +124,8 @@ def main() -> int:
     ap.add_argument("--shape", default="7b")
     ap.add_argument("--layers", type=int, default=0, help="0 = all layers of the shape")
     ap.add_argument("--sparsity", type=int, default=50)
-    ap.add_argument("--weights", default="f16", choices=["f16", "q4"])
+    ap.add_argument("--weights", default="f16", choices=["f16", "q4", "q4cl"],
+                    help="q4: 4-bit, groups of 32 input channels; q4cl: 4-bit, groups inside a channel's row")
     ap.add_argument("--group", type=int, default=1, help="cross-layer reuse group (1 = none)")
     ap.add_argument("--reuse-points", type=lambda s: int(s, 0), default=0b1111)
     ap.add_argument("--select", default="topk", choices=["topk", "threshold"],
@@ -168,7 +169,7 @@ def main() -> int:
     L = args.layers or base.n_layers
     shape = base
     sp = args.sparsity
-    kind = B.AF_W_F16 if args.weights == "f16" else B.AF_W_Q4G32
+    kind = {"f16": B.AF_W_F16, "q4": B.AF_W_Q4G32, "q4cl": B.AF_W_Q4CL}[args.weights]
     kv_len, kv_cap = args.kv_len, args.kv_len + 16
     widths = (shape.d_model, shape.n_heads * shape.head_dim, shape.d_model, shape.d_ffn)
     ks = tuple(keep_count(n, sp) for n in widths)
@@ -258,6 +259,8 @@ def main() -> int:
     active_bytes = sum(rows[l][p] * outs[p] for l in range(L) for p in range(4)) * bpw
     if kind == B.AF_W_Q4G32:   # every scale row is touched at these sparsities
         active_bytes += L * sum(widths[p] // 32 * outs[p] for p in range(4)) * 2
+    elif kind == B.AF_W_Q4CL:  # a channel's scales travel with its nibbles
+        active_bytes += sum(rows[l][p] * (outs[p] // 32) * 2 for l in range(L) for p in range(4))
 
     # ---- roofline of the dominant kernel ------------------------------------------------
     # The gate|up operator as it runs inside the step: one launch that builds
@@ -280,6 +283,8 @@ def main() -> int:
             ctx.select_gemv_f16(lay.Wgateup, h2, producer=B.AF_PRO_RMSNORM, gain=lay.g_ffn, eps=1e-5,
                                 sel_mode=B.AF_SEL_TOPK, k=ks[2], x_out=x2, idx_out=idx2,
                                 count_out=cnt2, y=y2)
+        elif kind == B.AF_W_Q4CL:
+            ctx.sparse_gemv_q4_cl(lay.Wgateup, lay.Sgateup, h2, st.sets[0].idx[2], nidx=ks[2], y=y2)
         else:
             ctx.sparse_gemv_q4(lay.Wgateup, lay.Sgateup, h2, st.sets[0].idx[2], nidx=ks[2], y=y2)
 
@@ -318,9 +323,12 @@ def main() -> int:
         if keep_frac is not None:
             alg -= rows2 * 4     # no index list travels through memory
             kname = "gemv_f16_kernel (gate|up: rmsnorm + per-range threshold + gathered GEMV)"
+    elif kind == B.AF_W_Q4CL:
+        alg = ks[2] * (shape.d_ffn + 2 * shape.d_ffn // 16 + 6) + 2 * shape.d_ffn * 2
+        kname = "gemv_q4_kernel, channel-local scales (gate|up, index set given)"
     else:
         alg = ks[2] * (shape.d_ffn + 6) + (shape.d_model // 32) * 2 * shape.d_ffn * 2 + 2 * shape.d_ffn * 2
-        kname = "gemv_q4_kernel (gate|up)"
+        kname = "gemv_q4_kernel (gate|up, index set given)"
     achieved = alg / (us_per_launch * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": kname,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -360,13 +368,16 @@ def main() -> int:
         wq = host_layer0
         if kind == B.AF_W_Q4G32:
             wq = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in host_layer0.items()}
+        elif kind == B.AF_W_Q4CL:
+            wq = {k: (O.quantize_q4_cl(v) if k.startswith("W") else v) for k, v in host_layer0.items()}
+        oq4 = {B.AF_W_F16: False, B.AF_W_Q4G32: True, B.AF_W_Q4CL: "cl"}[kind]
         n_done, t_cpu, h = 0, 0.0, h_host
         tr = None
         osel = O.SelectCfg(O.SEL_TOPK, ks) if keep_frac is None else O.SelectCfg(O.SEL_THRESHOLD, t=tuple(thr[0]))
         while n_done < 40 and t_cpu < 12.0:
             t1 = time.perf_counter()
             tr = O.decode_layer(ocfg, wq, h, K0.copy(), V0.copy(), kv_len, kv_len,
-                                osel, weights_q4=(kind == B.AF_W_Q4G32))
+                                osel, weights_q4=oq4)
             t_cpu += time.perf_counter() - t1
             n_done += 1
             if n_done == 1:

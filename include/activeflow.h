@@ -46,7 +46,7 @@ typedef enum {
 } af_status;
 
 enum { AF_F16 = 0, AF_F32 = 1 };                              /* y_kind            */
-enum { AF_W_F16 = 0, AF_W_Q4G32 = 1 };                        /* weight_kind       */
+enum { AF_W_F16 = 0, AF_W_Q4G32 = 1, AF_W_Q4CL = 2 };          /* weight_kind       */
 enum { AF_SEL_TOPK = 0, AF_SEL_THRESHOLD = 1, AF_SEL_DENSE = 2 }; /* selection mode */
 enum { AF_MAX_N = 32768, AF_MAX_BATCH = 8 };
 
@@ -91,11 +91,18 @@ int af_select_threshold(af_ctx* ctx, const void* x_f16, int n, float t, int32_t*
  *   channels per output: s = fp16(max|w| / 7), q = clamp(rint(w / s), -7, 7) (fp32
  *   arithmetic, ties to even, s == 0 -> q = 0), nibble = q + 8.
  *   packed u8 [in][ld/2]: byte i of row j = columns 2i (low nibble) and 2i+1 (high);
- *   scales fp16 [in/32][ld].  in % 32 == 0, out % 8 == 0, col0 % 8 == 0, ld % 8 == 0. */
+ *   scales fp16 [in/32][ld].  in % 32 == 0, out % 8 == 0, col0 % 8 == 0, ld % 8 == 0.
+ * af_pack_q4_cl: the channel-local arrangement (Section 6: the transposed matrix lets the
+ *   read of a channel bring all the scales it needs): the same quantiser with groups of 32
+ *   consecutive output columns inside one input channel's row.  packed as above; scales fp16
+ *   [in][ld/32].  out % 32 == 0, col0 % 32 == 0, ld % 32 == 0.  The bytes of an inactive
+ *   channel, scales included, are never read. */
 int af_pack_inmajor_f16(af_ctx* ctx, const void* W_f16, int out, int in, void* Wt, int ld,
                         int col0);
 int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
                    void* scales_f16, int ld, int col0);
+int af_pack_q4_cl(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
+                  void* scales_f16, int ld, int col0);
 
 /* ---- sparse GEMV: Section 4, operation C -----------------------------------------------
  * y[o] = sum over t < nidx of Wt[idx[t]][o] * x[idx[t]]  (+ residual[o] if given),
@@ -107,11 +114,14 @@ int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, void* packed
  *   y: fp16 or fp32 [out] by y_kind; residual: fp16 [out] or NULL; y may alias residual.
  * The result is deterministic: partial sums are combined in a fixed order.
  * af_sparse_gemv_q4: same with W = (nibble - 8) * scale of the row's group (layout of
- *   af_pack_q4_g32). */
+ *   af_pack_q4_g32); af_sparse_gemv_q4_cl: layout of af_pack_q4_cl. */
 int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, const void* x_f16,
                        const int32_t* idx, int nidx_host, const int32_t* nidx_dev, void* y,
                        int y_kind, const void* residual_f16);
 int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, int in, int out,
+                      int ld, const void* x_f16, const int32_t* idx, int nidx_host,
+                      const int32_t* nidx_dev, void* y, int y_kind, const void* residual_f16);
+int af_sparse_gemv_q4_cl(af_ctx* ctx, const void* packed, const void* scales_f16, int in, int out,
                       int ld, const void* x_f16, const int32_t* idx, int nidx_host,
                       const int32_t* nidx_dev, void* y, int y_kind, const void* residual_f16);
 
@@ -146,12 +156,13 @@ int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int l
 typedef struct {
   int d_model, n_heads, n_kv_heads, head_dim, d_ffn; /* head_dim must be 128 or 64 */
   float rms_eps, rope_theta;
-  int weight_kind; /* AF_W_F16 | AF_W_Q4G32 */
+  int weight_kind; /* AF_W_F16 | AF_W_Q4G32 | AF_W_Q4CL */
 } af_layer_cfg;
 
 /* In-major, fused: Wqkv [d][(h+2kv)*hd] (q|k|v), Wo [h*hd][d], Wgateup [d][2*ffn]
- * (gate|up), Wdown [ffn][d]; leading dimension == number of columns.  For AF_W_Q4G32 the
- * W* pointers are packed nibbles and S* their scales; S* are NULL for fp16 weights.
+ * (gate|up), Wdown [ffn][d]; leading dimension == number of columns.  For AF_W_Q4G32 and
+ * AF_W_Q4CL the W* pointers are packed nibbles and S* their scales (in the layout of the
+ * respective packer); S* are NULL for fp16 weights.
  * g_*: fp16 [d] RMSNorm gains. */
 typedef struct {
   const void *Wqkv, *Wo, *Wgateup, *Wdown;

@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libactiveflow.so")
 
 AF_F16, AF_F32 = 0, 1
-AF_W_F16, AF_W_Q4G32 = 0, 1
+AF_W_F16, AF_W_Q4G32, AF_W_Q4CL = 0, 1, 2
 AF_SEL_TOPK, AF_SEL_THRESHOLD, AF_SEL_DENSE = 0, 1, 2
 AF_SEL_SKIP_SETS = 1
 AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
@@ -26,7 +26,7 @@ AF_CALIB_BINS = 32768
 EXPORTS = [
     "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
     "af_set_workspace", "af_select_topk", "af_select_threshold", "af_pack_inmajor_f16",
-    "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_select_gemv_f16", "af_sparse_gemv_union_f16",
+    "af_pack_q4_g32", "af_sparse_gemv_f16", "af_sparse_gemv_q4", "af_sparse_gemv_q4_cl", "af_pack_q4_cl", "af_select_gemv_f16", "af_sparse_gemv_union_f16",
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
     "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
     "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         "af_pack_q4_g32": (i, [vp, vp, i, i, vp, vp, i, i]),
         "af_sparse_gemv_f16": (i, [vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
         "af_sparse_gemv_q4": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_sparse_gemv_q4_cl": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_pack_q4_cl": (i, [vp, vp, i, i, vp, vp, i, i]),
         "af_select_gemv_f16": (i, [vp, vp, i, i, i, i, vp, vp, f, i, i, f, vp, vp, vp, vp, i, vp]),
         "af_sparse_gemv_union_f16": (i, [vp, vp, i, i, i, vp, i, vp, i, vp, vp, vp, i]),
         "af_decode_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, vp,
@@ -215,6 +217,20 @@ class Context:
                "af_pack_q4_g32")
         return packed, scales
 
+    def pack_q4_cl(self, W, packed=None, scales=None, ld=None, col0=0):
+        """Channel-local groups: scales [in][ld/32]."""
+        out, n_in = W.shape
+        if packed is None:
+            ld = out if ld is None else ld
+            packed = torch.empty((n_in, ld // 2), dtype=torch.uint8, device=self.device)
+            scales = torch.empty((n_in, ld // 32), dtype=torch.float16, device=self.device)
+        ld = scales.shape[1] * 32
+        _check(lib().af_pack_q4_cl(self._h, _ptr(W, torch.float16, "W"), out, n_in,
+                                   _ptr(packed, torch.uint8, "packed"),
+                                   _ptr(scales, torch.float16, "scales"), ld, col0),
+               "af_pack_q4_cl")
+        return packed, scales
+
     # ---- GEMV ------------------------------------------------------------------------
     def sparse_gemv_f16(self, Wt, x, idx=None, nidx=None, nidx_dev=None, y=None, y_kind=AF_F16,
                         residual=None, out=None):
@@ -247,6 +263,23 @@ class Context:
             n_in, out, ld, _ptr(x, torch.float16, "x"), _ptr(idx, torch.int32, "idx"),
             int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"), _ptr(y, None, "y"), y_kind,
             _ptr(residual, torch.float16, "residual")), "af_sparse_gemv_q4")
+        return y
+
+    def sparse_gemv_q4_cl(self, packed, scales, x, idx=None, nidx=None, nidx_dev=None, y=None,
+                          y_kind=AF_F16, residual=None, out=None):
+        n_in = packed.shape[0]
+        ld = scales.shape[1] * 32
+        out = ld if out is None else out
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        if idx is not None and nidx is None:
+            nidx = idx.numel()
+        _check(lib().af_sparse_gemv_q4_cl(
+            self._h, _ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float16, "scales"),
+            n_in, out, ld, _ptr(x, torch.float16, "x"), _ptr(idx, torch.int32, "idx"),
+            int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"), _ptr(y, None, "y"), y_kind,
+            _ptr(residual, torch.float16, "residual")), "af_sparse_gemv_q4_cl")
         return y
 
     def select_gemv_f16(self, Wt, src, producer=AF_PRO_NONE, gain=None, eps=1e-5,

@@ -106,6 +106,7 @@ static inline bool af_plan_gemv_lds(const af_row_src& r, int max_rows, bool use_
 struct af_gemv_args {
   const void* W;          // fp16 in-major, or packed nibbles
   const half_t* scales;   // q4 only
+  bool q4_channel_local;  // q4: scales [in][ld/32] instead of [in/32][ld]
   int in, out, ld;
   af_row_src rows;
   void* y;

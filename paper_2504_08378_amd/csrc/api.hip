@@ -171,6 +171,48 @@ extern "C" int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, v
   return AF_OK;
 }
 
+// Channel-local groups: one thread quantises one (input channel, group of 32 output columns)
+// and writes the 16 packed bytes and the one scale of that group.  Consecutive threads take
+// consecutive input channels, so the reads of W[o][j] coalesce along j.
+__global__ __launch_bounds__(256) void pack_q4_cl_kernel(const half_t* W, int out, int in,
+                                                         unsigned char* packed, half_t* scales,
+                                                         int ld, int col0) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;  // input channel
+  const int g = blockIdx.y;                             // group of 32 output columns
+  if (j >= in) return;
+  float w[32];
+  float amax = 0.f;
+  for (int i = 0; i < 32; ++i) {
+    w[i] = (float)W[(size_t)(g * 32 + i) * in + j];
+    amax = fmaxf(amax, fabsf(w[i]));
+  }
+  const half_t sh = (half_t)(amax / 7.0f);
+  const float s = (float)sh;
+  scales[(size_t)j * (ld / 32) + col0 / 32 + g] = sh;
+  unsigned char* dst = packed + (size_t)j * (ld / 2) + (col0 + g * 32) / 2;
+  for (int i = 0; i < 32; i += 2) {
+    int q[2];
+    for (int e = 0; e < 2; ++e) {
+      float v = 0.f;
+      if (s != 0.f) v = fminf(7.f, fmaxf(-7.f, rintf(w[i + e] / s)));
+      q[e] = (int)v + 8;
+    }
+    dst[i / 2] = (unsigned char)(q[0] | (q[1] << 4));
+  }
+}
+
+extern "C" int af_pack_q4_cl(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
+                             void* scales_f16, int ld, int col0) {
+  if (!ctx || !W_f16 || !packed || !scales_f16) return AF_ENULL;
+  if (out <= 0 || in <= 0 || col0 < 0) return AF_EINVAL;
+  if (out % 32 || col0 % 32 || ld % 32 || col0 + out > ld) return AF_ESHAPE;
+  dim3 grid((in + 255) / 256, out / 32);
+  hipLaunchKernelGGL(pack_q4_cl_kernel, grid, dim3(256), 0, ctx->stream, (const half_t*)W_f16, out,
+                     in, (unsigned char*)packed, (half_t*)scales_f16, ld, col0);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
 // ---- bandwidth probe ---------------------------------------------------------------------
 typedef float probe_f4 __attribute__((ext_vector_type(4)));
 

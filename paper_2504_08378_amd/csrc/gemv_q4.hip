@@ -61,7 +61,9 @@ __device__ __forceinline__ void q4_fma8(float* acc, unsigned w, float x, float x
   acc[7] += (float)d[1] * x16;
 }
 
-template <int LX, int U, int NW>
+// CL = false: scales [in/32][ld], one per (group of 32 input channels, column);
+// CL = true:  scales [in][ld/32], one per (input channel, group of 32 columns).
+template <int LX, int U, int NW, bool CL>
 __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   constexpr int THREADS = NW * AF_WAVE;
   constexpr int LY = AF_WAVE / LX;
@@ -113,6 +115,13 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
     const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu));
     q4_fma8(acc, w, xv, xv * 0.0625f);
   };
+  // channel-local scales: the row's scale of this lane's column group multiplies x
+  const size_t srow = (size_t)(p.ld / 32);
+  const half_t* scol = p.scales + col_ld / 32;
+  auto consume_cl = [&](unsigned e, unsigned w, half_t s_row) {
+    const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu)) * (float)s_row;
+    q4_fma8(yacc, w, xv, xv * 0.0625f);
+  };
   // One pass over `cnt` staged rows: every (wave, lane group) slot takes a contiguous slice,
   // so it crosses few group boundaries.
   auto stream = [&](int cnt) {
@@ -121,27 +130,42 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
     const int iend = min(i + per, cnt);
     for (; i + U <= iend; i += U) {
       unsigned w[U], e[U];
+      half_t sr[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         e[u] = s_list[i + u];
         w[u] = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes);
+        if (CL) sr[u] = scol[(size_t)(e[u] >> 16) * srow];
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) consume(e[u], w[u]);
+      for (int u = 0; u < U; ++u) {
+        if (CL)
+          consume_cl(e[u], w[u], sr[u]);
+        else
+          consume(e[u], w[u]);
+      }
     }
     // Ragged end: one more batch of the same depth with the missing rows masked off, so its
     // loads are in flight together instead of one memory round trip per row.
     if (i < iend) {
       unsigned w[U], e[U];
+      half_t sr[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const bool ok = i + u < iend;
         e[u] = ok ? s_list[i + u] : 0u;
         w[u] = ok ? *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes) : 0u;
+        if (CL) sr[u] = ok ? scol[(size_t)(e[u] >> 16) * srow] : (half_t)0;
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (i + u < iend) consume(e[u], w[u]);
+      for (int u = 0; u < U; ++u) {
+        if (i + u < iend) {
+          if (CL)
+            consume_cl(e[u], w[u], sr[u]);
+          else
+            consume(e[u], w[u]);
+        }
+      }
     }
   };
 
@@ -170,8 +194,10 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
       stream(cnt);
     }
   }
+  if (!CL) {
 #pragma unroll
-  for (int c = 0; c < 8; ++c) yacc[c] += (float)sc[c] * acc[c];
+    for (int c = 0; c < 8; ++c) yacc[c] += (float)sc[c] * acc[c];
+  }
   __syncthreads();  // s_scratch changes its role: histograms -> wave sums
 
 #pragma unroll
@@ -219,26 +245,30 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
-#ifndef Q4_U
-#define Q4_U 8
-#endif
-template <int LX, int NW>
+template <int LX, int NW, bool CL>
 static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, Q4_U, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW, CL>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_q4_kernel<LX, Q4_U, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW, CL>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
 
 template <int LX>
-static void q4_launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
-  if (nw == 16)
-    q4_launch_one<LX, 16>(grid, lds, st, p);
-  else
-    q4_launch_one<LX, 4>(grid, lds, st, p);
+static void q4_launch_lx(int nw, bool cl, dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
+  if (nw == 16) {
+    if (cl)
+      q4_launch_one<LX, 16, true>(grid, lds, st, p);
+    else
+      q4_launch_one<LX, 16, false>(grid, lds, st, p);
+  } else {
+    if (cl)
+      q4_launch_one<LX, 4, true>(grid, lds, st, p);
+    else
+      q4_launch_one<LX, 4, false>(grid, lds, st, p);
+  }
 }
 
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
@@ -300,22 +330,23 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)
-    q4_launch_lx<64>(nw, grid, lds, ctx->stream, p);
+    q4_launch_lx<64>(nw, a.q4_channel_local, grid, lds, ctx->stream, p);
   else if (lx == 32)
-    q4_launch_lx<32>(nw, grid, lds, ctx->stream, p);
+    q4_launch_lx<32>(nw, a.q4_channel_local, grid, lds, ctx->stream, p);
   else
-    q4_launch_lx<16>(nw, grid, lds, ctx->stream, p);
+    q4_launch_lx<16>(nw, a.q4_channel_local, grid, lds, ctx->stream, p);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }
 
-extern "C" int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, int in,
-                                 int out, int ld, const void* x_f16, const int32_t* idx,
-                                 int nidx_host, const int32_t* nidx_dev, void* y, int y_kind,
-                                 const void* residual_f16) {
+static int sparse_gemv_q4_any(af_ctx* ctx, bool cl, const void* packed, const void* scales_f16,
+                              int in, int out, int ld, const void* x_f16, const int32_t* idx,
+                              int nidx_host, const int32_t* nidx_dev, void* y, int y_kind,
+                              const void* residual_f16) {
   if (!ctx || !packed || !scales_f16 || !x_f16 || !y) return AF_ENULL;
   if (in <= 0 || out <= 0 || in > AF_MAX_N) return AF_EINVAL;
-  if (in % 32 || out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
+  if (cl ? (out % 32 || ld % 32 || ld < out) : (in % 32 || out % 8 || ld % 8 || ld < out))
+    return AF_ESHAPE;
   if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
   if (idx == nullptr) {
     nidx_host = in;
@@ -327,6 +358,7 @@ extern "C" int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* sc
   af_gemv_args a{};
   a.W = packed;
   a.scales = (const half_t*)scales_f16;
+  a.q4_channel_local = cl;
   a.in = in;
   a.out = out;
   a.ld = ld;
@@ -341,4 +373,20 @@ extern "C" int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* sc
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;
   return af_launch_gemv_q4(ctx, a);
+}
+
+extern "C" int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, int in,
+                                 int out, int ld, const void* x_f16, const int32_t* idx,
+                                 int nidx_host, const int32_t* nidx_dev, void* y, int y_kind,
+                                 const void* residual_f16) {
+  return sparse_gemv_q4_any(ctx, false, packed, scales_f16, in, out, ld, x_f16, idx, nidx_host,
+                            nidx_dev, y, y_kind, residual_f16);
+}
+
+extern "C" int af_sparse_gemv_q4_cl(af_ctx* ctx, const void* packed, const void* scales_f16, int in,
+                                    int out, int ld, const void* x_f16, const int32_t* idx,
+                                    int nidx_host, const int32_t* nidx_dev, void* y, int y_kind,
+                                    const void* residual_f16) {
+  return sparse_gemv_q4_any(ctx, true, packed, scales_f16, in, out, ld, x_f16, idx, nidx_host,
+                            nidx_dev, y, y_kind, residual_f16);
 }

@@ -286,9 +286,15 @@ static int check_layer_args(const af_ctx* ctx, const af_layer_cfg* cfg, const af
   if (cfg->n_heads % cfg->n_kv_heads) return AF_ESHAPE;
   if (cfg->n_heads > AF_N_TICKETS - AF_TICKET_ATTN) return AF_ESHAPE;
   if (cfg->d_model % 8 || cfg->d_ffn % 8) return AF_ESHAPE;
-  if (cfg->weight_kind != AF_W_F16 && cfg->weight_kind != AF_W_Q4G32) return AF_EINVAL;
+  if (cfg->weight_kind != AF_W_F16 && cfg->weight_kind != AF_W_Q4G32 &&
+      cfg->weight_kind != AF_W_Q4CL)
+    return AF_EINVAL;
   const int qdim = cfg->n_heads * cfg->head_dim;
   if (cfg->weight_kind == AF_W_Q4G32 && (cfg->d_model % 32 || cfg->d_ffn % 32 || qdim % 32))
+    return AF_ESHAPE;
+  // channel-local groups run along the (fused) output columns
+  if (cfg->weight_kind == AF_W_Q4CL &&
+      (cfg->d_model % 32 || (2 * cfg->d_ffn) % 32 || ((cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->head_dim) % 32))
     return AF_ESHAPE;
   if (kv_len < 0 || kv_cap <= 0 || kv_len >= kv_cap || pos < 0) return AF_EINVAL;
   if (sel->mode != AF_SEL_TOPK && sel->mode != AF_SEL_THRESHOLD && sel->mode != AF_SEL_DENSE)
@@ -321,7 +327,7 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
   for (int i = 0; i < 7; ++i) act[i] = (half_t*)(ctx->ws + ctx->lay.act[i]);
   half_t *x0 = act[0], *qkv = act[1], *attn = act[2], *hmid = act[3], *x2 = act[4], *gu = act[5],
          *x3 = act[6];
-  const bool q4 = cfg->weight_kind == AF_W_Q4G32;
+  const bool q4 = cfg->weight_kind != AF_W_F16;
   int rc;
 
   struct Point {
@@ -350,6 +356,7 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
     af_gemv_args a{};
     a.W = W;
     a.scales = (const half_t*)Sc;
+    a.q4_channel_local = cfg->weight_kind == AF_W_Q4CL;
     a.in = in;
     a.out = out;
     a.ld = out;
@@ -401,7 +408,7 @@ static int check_layer_ptrs(const af_layer_cfg* cfg, const af_layer_weights* w,
                             const af_idx_sets* own, const af_idx_sets* src) {
   if (!w->Wqkv || !w->Wo || !w->Wgateup || !w->Wdown || !w->g_attn_norm || !w->g_ffn_norm)
     return AF_ENULL;
-  if (cfg->weight_kind == AF_W_Q4G32 && (!w->Sqkv || !w->So || !w->Sgateup || !w->Sdown))
+  if (cfg->weight_kind != AF_W_F16 && (!w->Sqkv || !w->So || !w->Sgateup || !w->Sdown))
     return AF_ENULL;
   for (int p = 0; p < 4; ++p) {
     const bool reused = (reuse >> p) & 1u;

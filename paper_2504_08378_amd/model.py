@@ -45,6 +45,9 @@ class DeviceLayer:
             if weight_kind == B.AF_W_F16:
                 Wt = torch.empty((n_in, ld), dtype=torch.float16, device=dev)
                 S = None
+            elif weight_kind == B.AF_W_Q4CL:
+                Wt = torch.empty((n_in, ld // 2), dtype=torch.uint8, device=dev)
+                S = torch.empty((n_in, ld // 32), dtype=torch.float16, device=dev)
             else:
                 Wt = torch.empty((n_in, ld // 2), dtype=torch.uint8, device=dev)
                 S = torch.empty((n_in // 32, ld), dtype=torch.float16, device=dev)
@@ -54,6 +57,8 @@ class DeviceLayer:
                 torch.cuda.current_stream().synchronize()
                 if weight_kind == B.AF_W_F16:
                     ctx.pack_inmajor_f16(Wd, Wt, col0=col)
+                elif weight_kind == B.AF_W_Q4CL:
+                    ctx.pack_q4_cl(Wd, Wt, S, col0=col)
                 else:
                     ctx.pack_q4_g32(Wd, Wt, S, col0=col)
                 ctx.synchronize()

@@ -280,18 +280,26 @@ def test_7b_layer_full_size_stage_by_stage(ctx):
         assert _sets_close(got, tr.idx[p], tr.x[p]), p
 
 
-@pytest.mark.parametrize("sp", [50, 70])
-def test_layer_q4_weights(ctx, sp):
-    """4-bit group-32 weights: the device packer's bits feed the GPU, the oracle quantises
-    the same fp16 matrices with its own quantiser (bit-equality of the two is checked in
+def _fused_cl(layer):
+    """Channel-local groups follow the fused column layout (q|k|v, gate|up): quantise each
+    operator on its own, which is the same thing because every part is a multiple of 32 wide."""
+    return {k: (O.quantize_q4_cl(v) if k.startswith("W") else v) for k, v in layer.items()}
+
+
+@pytest.mark.parametrize("sp,kind", [(50, B.AF_W_Q4G32), (70, B.AF_W_Q4G32), (50, B.AF_W_Q4CL)])
+def test_layer_q4_weights(ctx, sp, kind):
+    """4-bit weights: the device packer's bits feed the GPU, the oracle quantises the same
+    fp16 matrices with its own quantiser (bit-equality of the two is checked in
     test_gpu_q4), then the layer is compared as in the fp16 case."""
     shape = S.MODEL_SHAPES["tiny_gqa"]
     layers, kv, h = _host_stack(shape, 1, seed=5)
     ks = _ks(shape, sp)
-    wq = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in layers[0].items()}
+    cl = kind == B.AF_W_Q4CL
+    wq = _fused_cl(layers[0]) if cl else {k: (O.quantize_q4_g32(v) if k.startswith("W") else v)
+                                           for k, v in layers[0].items()}
     tr = O.decode_layer(_ocfg(shape), wq, h, kv[0][0].copy(), kv[0][1].copy(), KV_LEN, KV_LEN,
-                        O.SelectCfg(O.SEL_TOPK, ks), weights_q4=True)
-    st = _dev_stack(ctx, shape, layers, kv, kind=B.AF_W_Q4G32)
+                        O.SelectCfg(O.SEL_TOPK, ks), weights_q4="cl" if cl else True)
+    st = _dev_stack(ctx, shape, layers, kv, kind=kind)
     hin = to_dev(h); hout = torch.zeros_like(hin)
     # forced sets
     st.sets[0].load(tr.idx)

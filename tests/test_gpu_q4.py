@@ -78,3 +78,53 @@ def test_q4_7b_down_shape_sampled(ctx):
         nib, s = O.quantize_q4_g32(W[rows])
         ref = O.sparse_gemv_q4(nib, s, x, idx)
         assert np.max(np.abs(to_host(y)[rows] - ref)) <= 1e-4 * np.sqrt(np.mean(ref ** 2))
+
+
+# ---- channel-local groups (scales inside a channel's row) ---------------------------------
+@pytest.mark.parametrize("out,n", [(32, 8), (160, 96), (1056, 640), (4096, 2048)])
+def test_cl_pack_matches_oracle_quantiser_bit_for_bit(ctx, out, n):
+    W, _ = _case(out, n, 2)
+    if out >= 160:
+        W[32:64, 3] = 0
+        W[0:32, 5] = 0; W[7, 5] = -0.75
+        W[32:64, 6] = np.float16(6e-8)
+    packed, scales = ctx.pack_q4_cl(to_dev(W))
+    ctx.synchronize()
+    nib, s = O.quantize_q4_cl(W)
+    assert np.array_equal(to_host(scales).view(np.uint16), s.view(np.uint16))
+    assert np.array_equal(to_host(packed), O.pack_q4(nib))
+
+
+def test_cl_pack_fused_columns(ctx):
+    """Two operators side by side (as q|k|v and gate|up are stored): each keeps its own groups."""
+    Wa, _ = _case(64, 96, 3); Wb, _ = _case(96, 96, 4)
+    import torch
+    packed = torch.zeros((96, 80), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((96, 5), dtype=torch.float16, device="cuda")
+    ctx.pack_q4_cl(to_dev(Wa), packed, scales, col0=0)
+    ctx.pack_q4_cl(to_dev(Wb), packed, scales, col0=64)
+    ctx.synchronize()
+    na, sa = O.quantize_q4_cl(Wa); nb, sb = O.quantize_q4_cl(Wb)
+    assert np.array_equal(to_host(packed), np.concatenate([O.pack_q4(na), O.pack_q4(nb)], axis=1))
+    assert np.array_equal(to_host(scales).view(np.uint16), np.concatenate([sa, sb], axis=1).view(np.uint16))
+
+
+@pytest.mark.parametrize("out,n,k", [(32, 8, 3), (160, 96, 48), (544, 768, 300), (1056, 640, 640),
+                                     (4096, 2048, 1024), (12288, 1024, 307), (22016, 256, 128),
+                                     (4096, 11008, 5511)])
+def test_cl_gemv(ctx, out, n, k):
+    W, x = _case(out, n, out + n + 1)
+    nib, s = O.quantize_q4_cl(W)
+    idx = O.select_topk(x, k)
+    packed, scales = ctx.pack_q4_cl(to_dev(W))
+    ref = O.sparse_gemv_q4_cl(nib, s, x, idx)
+    for kind, tol in ((B.AF_F32, 1e-4), (B.AF_F16, TOL)):
+        y = ctx.sparse_gemv_q4_cl(packed, scales, to_dev(x), to_dev(idx), y_kind=kind)
+        ctx.synchronize()
+        assert O.rel_err(to_host(y), ref) <= tol, kind
+    res = S.activation(3, S.channel_scales(3, out, "q4res"), "q4res", 0)
+    y = ctx.sparse_gemv_q4_cl(packed, scales, to_dev(x), None, residual=to_dev(res))
+    ctx.synchronize()
+    assert O.rel_err(to_host(y), O.sparse_gemv_q4_cl(nib, s, x, np.arange(n)) + res.astype(np.float64)) <= TOL
+    with pytest.raises(B.AfError):
+        ctx.sparse_gemv_q4_cl(packed, scales, to_dev(x), None, out=out - 8)      # out % 32 != 0
