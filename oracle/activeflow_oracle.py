@@ -23,7 +23,9 @@ What it follows (ActiveFlow, arXiv 2504.08378):
     functions (the quantiser itself is this build's own definition, see below);
     quantize_q4_cl is the arrangement with the groups inside a channel's row.
   * Fig. "simplified transformer layer" (Section 2.2): pre-norm block with
-    residual connections -> decode_layer.
+    residual connections -> decode_layer; the same block with a mixture-of-experts
+    feed-forward half (the Mixtral-8x7B deployment of Sections 1 and 7)
+    -> moe_route, decode_moe_layer.
   * Eq. 9: sparsity sp is the fraction of channels dropped -> keep_count.
 
 Readings taken where the paper is silent: ties go to the lower channel index;
@@ -343,21 +345,11 @@ def _linear(W, x16, idx, weights_q4):
     return sparse_gemv(W, x16, idx)
 
 
-def decode_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
-                 sel: SelectCfg, sets=None, weights_q4: bool = False) -> LayerTrace:
-    """One batch-1 decode step of a pre-norm block with activation sparsity at the
-    inputs of qkv, o, gate/up and down.
-
-    w holds out-major matrices Wq, Wk, Wv, Wo, Wgate, Wup, Wdown (fp16, or
-    (nib, scales) pairs when weights_q4) and gains g_attn, g_ffn.  K, V
-    [n_kv][cap][hd] fp16 are updated in place at slot kv_len.  `sets` gives the
-    index sets for points whose reuse bit is set.  Returns the stage trace.
-    """
-    tr = LayerTrace()
-    h0 = np.asarray(hidden, dtype=np.float16)
+def _attention_block(cfg, w, h0, K, V, kv_len, pos, sel, sets, weights_q4, tr):
+    """The attention half of the block: norm, selection, q|k|v, rotary embedding, cache
+    append, attention, selection, output projection, residual add.  Fills the trace's
+    attention-side fields and returns h_mid (fp16)."""
     nh, nkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
-
-    # attention block
     x0 = round_f16(rmsnorm(h0, w["g_attn"], cfg.rms_eps))
     i0 = _select(x0, P_QKV, sel, sets)
     q = _linear(w["Wq"], x0, i0, weights_q4)
@@ -374,6 +366,26 @@ def decode_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
     a16 = round_f16(attention_decode(qr, K, V, kv_len + 1).reshape(-1))
     i1 = _select(a16, P_O, sel, sets)
     h1 = round_f16(h0.astype(np.float64) + _linear(w["Wo"], a16, i1, weights_q4))
+    tr.x[:2] = [x0, a16]
+    tr.idx[:2] = [i0, i1]
+    tr.qkv, tr.attn, tr.h_mid = qkv16, a16, h1
+    tr.k_new, tr.v_new = k_new, v16.copy()
+    return h1
+
+
+def decode_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
+                 sel: SelectCfg, sets=None, weights_q4: bool = False) -> LayerTrace:
+    """One batch-1 decode step of a pre-norm block with activation sparsity at the
+    inputs of qkv, o, gate/up and down.
+
+    w holds out-major matrices Wq, Wk, Wv, Wo, Wgate, Wup, Wdown (fp16, or
+    (nib, scales) pairs when weights_q4) and gains g_attn, g_ffn.  K, V
+    [n_kv][cap][hd] fp16 are updated in place at slot kv_len.  `sets` gives the
+    index sets for points whose reuse bit is set.  Returns the stage trace.
+    """
+    tr = LayerTrace()
+    h0 = np.asarray(hidden, dtype=np.float16)
+    h1 = _attention_block(cfg, w, h0, K, V, kv_len, pos, sel, sets, weights_q4, tr)
 
     # feed-forward block
     x2 = round_f16(rmsnorm(h1, w["g_ffn"], cfg.rms_eps))
@@ -386,10 +398,73 @@ def decode_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
     i3 = _select(x3, P_DOWN, sel, sets)
     h2 = round_f16(h1.astype(np.float64) + _linear(w["Wdown"], x3, i3, weights_q4))
 
-    tr.x = [x0, a16, x2, x3]
-    tr.idx = [i0, i1, i2, i3]
-    tr.qkv, tr.attn, tr.h_mid, tr.gateup, tr.hidden = qkv16, a16, h1, gu16, h2
-    tr.k_new, tr.v_new = k_new, v16.copy()
+    tr.x[2:] = [x2, x3]
+    tr.idx[2:] = [i2, i3]
+    tr.gateup, tr.hidden = gu16, h2
+    return tr
+
+
+# --------------------------------------------------------------------------
+# mixture-of-experts block (the Mixtral-8x7B deployment of Sections 1 and 7)
+# --------------------------------------------------------------------------
+def moe_route(x16, Wr, top: int = 2):
+    """Router of a sparse mixture-of-experts block: logits = Wr x over all channels of the
+    normed input (the router is tiny and stays dense), the `top` experts of largest logit
+    (ties to the lower expert index), slot 0 the largest; weights = softmax over the chosen
+    logits.  Returns (experts int32 [top], weights fp64 [top], logits fp64 [E])."""
+    logits = np.asarray(Wr, dtype=np.float16).astype(np.float64) @ np.asarray(x16, np.float16).astype(np.float64)
+    order = np.lexsort((np.arange(len(logits)), -logits))[:top]
+    z = logits[order]
+    e = np.exp(z - z.max())
+    return order.astype(np.int32), e / e.sum(), logits
+
+
+@dataclass
+class MoeTrace(LayerTrace):
+    experts: np.ndarray = None      # int32 [top], slot order
+    weights: np.ndarray = None      # fp64 [top]
+    logits: np.ndarray = None       # fp64 [E]
+    x_down: list = None             # fp16 [ffn] per slot: silu(gate) * up of that expert
+    idx_down: list = None           # int32 index set per slot
+    h_slots: list = None            # fp16 [d]: residual stream after each slot's expert
+
+
+def decode_moe_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
+                     sel: SelectCfg, top: int = 2) -> MoeTrace:
+    """Decode step of a block whose feed-forward half is a sparse mixture of experts.
+
+    The paper deploys Mixtral-8x7B with its method but gives no MoE-specific rule, so the
+    dense block's rules are carried over (readings): operations T and C sit in front of
+    every linear operator; the normed input is shared by the router and by all experts'
+    gate/up projections, so one selection at point 2 serves every chosen expert; each
+    chosen expert's down projection selects on its own silu(gate)*up (point 3, the same k
+    or threshold for every expert).  Expert outputs are added to the fp16 residual stream
+    one slot at a time, weighted by the router: h <- fp16(h + w_s * down_s(...)).
+
+    w: the attention-side keys of decode_layer, g_ffn, Wr [E][d], and lists Wgate[e],
+    Wup[e] [ffn][d], Wdown[e] [d][ffn]."""
+    tr = MoeTrace()
+    h0 = np.asarray(hidden, dtype=np.float16)
+    h1 = _attention_block(cfg, w, h0, K, V, kv_len, pos, sel, None, False, tr)
+    x2 = round_f16(rmsnorm(h1, w["g_ffn"], cfg.rms_eps))
+    experts, weights, logits = moe_route(x2, w["Wr"], top)
+    i2 = _select(x2, P_GATEUP, sel, None)
+    f = cfg.d_ffn
+    h = h1
+    tr.x_down, tr.idx_down, tr.h_slots, gus = [], [], [], []
+    for s, e in enumerate(experts):
+        g = sparse_gemv(w["Wgate"][e], x2, i2)
+        u = sparse_gemv(w["Wup"][e], x2, i2)
+        gu16 = round_f16(np.concatenate([g, u]))
+        x3 = round_f16(silu(gu16[:f]) * gu16[f:].astype(np.float64))
+        i3 = _select(x3, P_DOWN, sel, None)
+        h = round_f16(h.astype(np.float64) + weights[s] * sparse_gemv(w["Wdown"][e], x3, i3))
+        gus.append(gu16); tr.x_down.append(x3); tr.idx_down.append(i3); tr.h_slots.append(h)
+    tr.x[2:] = [x2, tr.x_down[0]]
+    tr.idx[2:] = [i2, tr.idx_down[0]]
+    tr.gateup = np.concatenate(gus)
+    tr.experts, tr.weights, tr.logits = experts, weights, logits
+    tr.hidden = h
     return tr
 
 

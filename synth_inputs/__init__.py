@@ -24,8 +24,10 @@ from .generators import (  # noqa: F401
     channel_scales,
     device_kv_cache,
     device_layer_weights,
+    device_moe_layer_weights,
     kv_cache,
     layer_weights,
+    moe_layer_weights,
     norm_gain,
     rng_for,
     weight_matrix,

@@ -19,6 +19,7 @@ class ModelShape:
     n_kv_heads: int
     head_dim: int
     d_ffn: int
+    n_experts: int = 0      # > 0: the feed-forward half is a mixture of experts of width d_ffn
 
     @property
     def qkv_out(self) -> int:
@@ -37,6 +38,9 @@ MODEL_SHAPES = {
     "7b": ModelShape("7b", 32, 4096, 32, 32, 128, 11008),
     "13b": ModelShape("13b", 40, 5120, 40, 40, 128, 13824),
     "70b": ModelShape("70b", 1, 8192, 64, 8, 128, 28672),
+    # mixture-of-experts blocks: a toy and the Mixtral-8x7B block (8 experts, top-2)
+    "tiny_moe": ModelShape("tiny_moe", 2, 512, 8, 2, 64, 1376, n_experts=4),
+    "mixtral": ModelShape("mixtral", 32, 4096, 32, 8, 128, 14336, n_experts=8),
 }
 
 
@@ -133,6 +137,43 @@ def layer_weights(seed: int, shape: ModelShape, layer: int, threads: int = 1) ->
         "g_attn": norm_gain(seed, d, shape.name, layer, "attn"),
         "g_ffn": norm_gain(seed, d, shape.name, layer, "ffn"),
     }
+
+
+def moe_layer_weights(seed: int, shape: ModelShape, layer: int, threads: int = 1) -> dict:
+    """A layer whose feed-forward half is a mixture of shape.n_experts experts: the
+    attention-side tensors of layer_weights(), g_ffn, the router Wr [E][d] ~ N(0, 0.02) and
+    per-expert lists Wgate[e], Wup[e] [ffn][d], Wdown[e] [d][ffn]."""
+    d, f, hd, E = shape.d_model, shape.d_ffn, shape.head_dim, shape.n_experts
+    nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
+    mk = lambda name, o, i: weight_matrix(seed, o, i, shape.name, layer, name, threads=threads)
+    return {
+        "Wq": mk("q", nq, d), "Wk": mk("k", nkv, d), "Wv": mk("v", nkv, d), "Wo": mk("o", d, nq),
+        "Wr": mk("router", E, d),
+        "Wgate": [mk(f"gate{e}", f, d) for e in range(E)],
+        "Wup": [mk(f"up{e}", f, d) for e in range(E)],
+        "Wdown": [mk(f"down{e}", d, f) for e in range(E)],
+        "g_attn": norm_gain(seed, d, shape.name, layer, "attn"),
+        "g_ffn": norm_gain(seed, d, shape.name, layer, "ffn"),
+    }
+
+
+def device_moe_layer_weights(seed: int, shape: ModelShape, layer: int, device="cuda") -> dict:
+    """moe_layer_weights() drawn on the GPU (same distributions, torch's generator)."""
+    import torch
+
+    base = device_layer_weights(seed, shape, layer, device)
+    d, f, E = shape.d_model, shape.d_ffn, shape.n_experts
+    gen = torch.Generator(device=device)
+
+    def mk(name, o, i):
+        gen.manual_seed((int(seed) * 1000003 + zlib.crc32(f"{shape.name}/{layer}/{name}".encode())) & 0x7FFFFFFFFFFFFFFF)
+        return (torch.randn((o, i), generator=gen, device=device, dtype=torch.float32) * 0.02).to(torch.float16)
+
+    base["Wr"] = mk("router", E, d)
+    base["Wgate"] = [base["Wgate"]] + [mk(f"gate{e}", f, d) for e in range(1, E)]
+    base["Wup"] = [base["Wup"]] + [mk(f"up{e}", f, d) for e in range(1, E)]
+    base["Wdown"] = [base["Wdown"]] + [mk(f"down{e}", d, f) for e in range(1, E)]
+    return base
 
 
 def device_layer_weights(seed: int, shape: ModelShape, layer: int, device="cuda") -> dict:
