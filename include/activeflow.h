@@ -213,6 +213,50 @@ int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
                     const af_select_cfg* sel, int n_sel, int group, unsigned reuse_points,
                     af_idx_sets* sets);
 
+/* ---- mixture-of-experts block (the Mixtral-8x7B deployment reported in Sections 1 and 7):
+ * the feed-forward half is n_experts experts of width d_ffn, of which a router picks `top`
+ * per token.  The paper gives no MoE-specific rule; the dense block's rules are carried over:
+ * operations T and C sit in front of every linear operator; the normed input is shared by the
+ * router (dense: it is tiny) and by the gate/up projections of all chosen experts, so one
+ * selection (point 2) serves them all; every chosen expert's down projection selects on its
+ * own silu(gate)*up with sel->k[3] / sel->t[3].  Router: logits = Wr x in fp32, the `top`
+ * largest (ties to the lower expert), slot 0 the largest; weights = softmax over the chosen
+ * logits.  hidden <- fp16(hidden + weight_s * down_s(...)), one slot after the other.
+ * The experts are reached on the device (no host round trip): the call can be captured. */
+enum { AF_MOE_MAX_EXPERTS = 16, AF_MOE_MAX_TOP = 4 };
+typedef struct {
+  af_layer_cfg base; /* d_ffn: width of one expert; weight_kind must be AF_W_F16 */
+  int n_experts, top;
+} af_moe_cfg;
+/* Wqkv, Wo, g_*: as af_layer_weights.  Wr fp16 [n_experts][d] (one row per expert).
+ * Wgateup fp16 [n_experts][d][2*ffn]: expert e's in-major gate|up matrix at element offset
+ * e*d*2*ffn; Wdown fp16 [n_experts][ffn][d] likewise. */
+typedef struct {
+  const void *Wqkv, *Wo, *g_attn_norm, *g_ffn_norm;
+  const void *Wr, *Wgateup, *Wdown;
+} af_moe_weights;
+/* Index sets: points 0 qkv, 1 o, 2 gate/up (shared by the chosen experts), 3+s the down
+ * projection of slot s.  Written unless sel->flags has AF_SEL_SKIP_SETS (then they may be
+ * NULL).  idx[p] holds as many entries as the point has input channels. */
+typedef struct {
+  int32_t* idx[3 + AF_MOE_MAX_TOP];
+  int32_t* count[3 + AF_MOE_MAX_TOP];
+} af_moe_sets;
+/* Router results of the call (device memory, all required): experts int32 [top] in slot
+ * order, weights fp32 [top], logits fp32 [n_experts]. */
+typedef struct {
+  int32_t* experts;
+  float* weights;
+  float* logits;
+} af_moe_route;
+/* One batch-1 decode step of such a block; arguments as af_decode_layer.  sel->reuse_mask
+ * must be 0.  af_layer_tap afterwards: 5 = gate|up of the chosen experts [top][2*ffn],
+ * 6 = x_down [top][ffn]; the workspace limits must cover top*2*ffn outputs. */
+int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* cfg, const af_moe_weights* w,
+                        const void* hidden_in, void* hidden_out, void* k_cache, void* v_cache,
+                        int kv_len, int kv_cap, int pos, const af_select_cfg* sel,
+                        const af_moe_sets* sets, const af_moe_route* route);
+
 /* Device address of an inter-operator tensor of the most recent af_decode_layer call on
  * this context (for tests): which = 0 x_qkv [d], 1 qkv [(h+2kv)*hd], 2 attn [h*hd],
  * 3 h_mid [d], 4 x_gateup [d], 5 gateup [2*ffn], 6 x_down [ffn].  fp16. */

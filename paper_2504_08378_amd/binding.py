@@ -30,7 +30,9 @@ EXPORTS = [
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
     "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
     "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
+    "af_decode_moe_layer",
 ]
+AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
 
 class AfError(RuntimeError):
@@ -58,6 +60,23 @@ class IdxSets(C.Structure):
 class SelectCfg(C.Structure):
     _fields_ = [("mode", C.c_int), ("k", C.c_int * 4), ("t", C.c_float * 4),
                 ("reuse_mask", C.c_uint), ("flags", C.c_uint)]
+
+
+class MoeCfg(C.Structure):
+    _fields_ = [("base", LayerCfg), ("n_experts", C.c_int), ("top", C.c_int)]
+
+
+class MoeWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("Wqkv", "Wo", "g_attn_norm", "g_ffn_norm", "Wr", "Wgateup", "Wdown")]
+
+
+class MoeSets(C.Structure):
+    _fields_ = [("idx", C.c_void_p * (3 + AF_MOE_MAX_TOP)), ("count", C.c_void_p * (3 + AF_MOE_MAX_TOP))]
+
+
+class MoeRoute(C.Structure):
+    _fields_ = [("experts", C.c_void_p), ("weights", C.c_void_p), ("logits", C.c_void_p)]
 
 
 _lib = None
@@ -106,6 +125,9 @@ def lib() -> C.CDLL:
         "af_calib_accumulate": (i, [vp, vp, i, vp]),
         "af_calib_accumulate_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(vp)]),
         "af_calib_thresholds": (i, [vp, vp, C.POINTER(C.c_int), i, vp]),
+        "af_decode_moe_layer": (i, [vp, C.POINTER(MoeCfg), C.POINTER(MoeWeights), vp, vp, vp, vp,
+                                    i, i, i, C.POINTER(SelectCfg), C.POINTER(MoeSets),
+                                    C.POINTER(MoeRoute)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -335,6 +357,14 @@ class Context:
             self._h, C.byref(cfg), w_array, n_layers, _ptr(hidden_in, torch.float16, "hidden_in"),
             _ptr(hidden_out, torch.float16, "hidden_out"), k_ptrs, v_ptrs, kv_len, kv_cap, pos,
             sel_arr, n_sel, group, reuse_points, sets_array), "af_decode_stack")
+
+    def decode_moe_layer(self, cfg: MoeCfg, w: MoeWeights, hidden_in, hidden_out, k_cache, v_cache,
+                         kv_len: int, kv_cap: int, pos: int, sel: SelectCfg, sets, route: MoeRoute):
+        _check(lib().af_decode_moe_layer(
+            self._h, C.byref(cfg), C.byref(w), _ptr(hidden_in, torch.float16, "hidden_in"),
+            _ptr(hidden_out, torch.float16, "hidden_out"), _ptr(k_cache, torch.float16, "k_cache"),
+            _ptr(v_cache, torch.float16, "v_cache"), kv_len, kv_cap, pos, C.byref(sel),
+            C.byref(sets) if sets is not None else None, C.byref(route)), "af_decode_moe_layer")
 
     def layer_tap(self, which: int, n: int):
         """fp16 view (a copy) of an inter-operator tensor of the last decode_layer call."""

@@ -112,6 +112,13 @@ struct af_gemv_args {
   void* y;
   int y_kind;
   const half_t* residual;
+  // Device-selected matrices (mixture of experts): the out columns form n_slots equal slots;
+  // slot s uses the matrix at W + w_sel[s] * w_stride elements (leading dimension ld), w_sel
+  // being device memory.  w_sel == null: one matrix, one slot.
+  const int32_t* w_sel;
+  long long w_stride;
+  int n_slots;
+  const float* y_scale;  // device scalar multiplying the product before the residual (null: 1)
 };
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);

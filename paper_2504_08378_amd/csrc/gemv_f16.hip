@@ -31,9 +31,19 @@ struct GemvParams {
   int out, ld, y_kind, out_pad, use_lds_x;
   int range_sel;  // threshold selection per channel range, no list for the whole vector
   int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
+  // Output columns come in `slots` of cols_per_slot columns, each covered by tiles_per_slot
+  // tiles.  A plain GEMV has one slot.  With w_sel, slot s multiplies by the matrix
+  // W + w_sel[s] * w_stride (leading dimension ld), so the experts a router picked on the
+  // device are reached without a host round trip.  y_scale (device, one float) scales the
+  // product before the residual is added.
+  int cols_per_slot, tiles_per_slot;
+  const int* w_sel;
+  long long w_stride;
+  const float* y_scale;
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
+  if (p.y_scale) v *= *p.y_scale;
   if (p.residual) v += (float)p.residual[col];
   if (p.y_kind == AF_F16)
     reinterpret_cast<half_t*>(p.y)[col] = (half_t)v;
@@ -60,8 +70,11 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
-  const int col = blockIdx.x * TW + lx * 8;
-  const int col_ld = col < p.out ? col : 0;  // lanes past the edge read column 0 and are dropped
+  const int slot = blockIdx.x / p.tiles_per_slot;
+  const int tile_in = blockIdx.x - slot * p.tiles_per_slot;   // tile inside the slot
+  const int col = tile_in * TW + lx * 8;                       // column inside the slot
+  // lanes past the slot's edge read the tile's first column and are dropped at the store
+  const int col_ld = col < p.cols_per_slot ? col : tile_in * TW;
   const int S = gridDim.y, s = blockIdx.y;
   const af_row_src& r = p.rows;
 
@@ -88,6 +101,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   const half_t* wcol = p.W + col_ld;
+  if (p.w_sel) wcol += (size_t)p.w_sel[slot] * (size_t)p.w_stride;
 
   // One pass over `cnt` staged rows of s_list.
   auto stream = [&](int cnt) {
@@ -183,15 +197,15 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   }
   __syncthreads();
 
-  const int tile0 = blockIdx.x * TW;
+  const int tile0 = blockIdx.x * TW;                      // in the padded column space
+  const int out0 = slot * p.cols_per_slot + tile_in * TW;  // first output column of the tile
+  const int valid = min(TW, p.cols_per_slot - tile_in * TW);
   if (S == 1) {
-    for (int c = tid; c < TW; c += GEMV_THREADS) {
-      if (tile0 + c < p.out) {
-        float v = 0.f;
+    for (int c = tid; c < valid; c += GEMV_THREADS) {
+      float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < GEMV_WAVES; ++w) v += s_red[w][c];
-        store_out(p, tile0 + c, v);
-      }
+      for (int w = 0; w < GEMV_WAVES; ++w) v += s_red[w][c];
+      store_out(p, out0 + c, v);
     }
     return;
   }
@@ -211,11 +225,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   }
   __syncthreads();
   if (!s_last) return;
-  for (int c = tid; c < TW; c += GEMV_THREADS) {
-    if (tile0 + c < p.out) {
-      store_out(p, tile0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
-    }
-  }
+  for (int c = tid; c < valid; c += GEMV_THREADS)
+    store_out(p, out0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
 }
 
@@ -292,9 +303,17 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   int lx, nw, S;
   choose_config(ctx, a.out, max_rows, r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, &lx, &nw, &S);
   const int tw = lx * 8;
-  const int tiles = (a.out + tw - 1) / tw;
+  // output slots (one per device-selected matrix; a single one otherwise), whole tiles each
+  const int n_slots = a.w_sel ? a.n_slots : 1;
+  if (n_slots < 1 || a.out % n_slots) return AF_EINVAL;
+  const int cols_per_slot = a.out / n_slots;
+  if (cols_per_slot % 8) return AF_ESHAPE;
+  const int tiles_per_slot = (cols_per_slot + tw - 1) / tw;
+  const int tiles = n_slots * tiles_per_slot;
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
+  S = (int)((long long)S * ((a.out + tw - 1) / tw) / tiles);  // padding adds tiles: keep the grid size
+  if (S < 1) S = 1;
   const bool range_sel = r.sel == AF_SEL_THRESHOLD && !r.idx_out && !r.count_out;
   const bool use_lds_x = r.pro != AF_PRO_NONE || r.sel != AF_ROWS_GIVEN;
   size_t xs_bytes;
@@ -318,6 +337,11 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.use_lds_x = use_lds_x ? 1 : 0;
   p.range_sel = range_sel ? 1 : 0;
   p.list_off = (int)xs_bytes;
+  p.cols_per_slot = cols_per_slot;
+  p.tiles_per_slot = tiles_per_slot;
+  p.w_sel = a.w_sel;
+  p.w_stride = a.w_stride;
+  p.y_scale = a.y_scale;
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

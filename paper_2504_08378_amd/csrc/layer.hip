@@ -15,6 +15,7 @@
 #include <math.h>
 
 #include "af_internal.h"
+#include "row_prologue.h"
 
 #define ATT_THREADS 256
 #define ATT_WAVES (ATT_THREADS / AF_WAVE)
@@ -479,6 +480,191 @@ extern "C" int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_la
     rc = run_layer(ctx, cfg, &w[l], hin, (half_t*)hidden_out, k_caches[l], v_caches[l], kv_len,
                    kv_cap, pos, sl, reuse, write_sets, own, src);
     if (rc) return rc;
+  }
+  return AF_OK;
+}
+
+// ---- mixture-of-experts block ------------------------------------------------------------
+#define MOE_THREADS 1024
+struct RouterParams {
+  af_row_src rows;  // RMSNorm of h_mid: the same x the gate/up GEMV builds
+  const half_t* Wr;
+  int n_experts, top;
+  int32_t* experts;
+  float* weights;
+  float* logits;
+};
+
+// Router of one token: x in LDS, one fp32 dot product per expert (lanes -> waves -> one
+// thread, fixed order), then the `top` largest logits and their softmax.
+__global__ __launch_bounds__(MOE_THREADS) void moe_router_kernel(RouterParams p) {
+  typedef RowPrologue<MOE_THREADS> RP;
+  extern __shared__ __align__(16) unsigned short xs[];
+  __shared__ typename RP::Smem s_rp;
+  __shared__ float s_part[MOE_THREADS / AF_WAVE][AF_MOE_MAX_EXPERTS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  RP::produce(p.rows, xs, s_rp, false, 0, 1);
+  const int nvec = p.rows.n >> 3;
+  const half8* xv = reinterpret_cast<const half8*>(xs);
+  float acc[AF_MOE_MAX_EXPERTS];
+#pragma unroll
+  for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e) acc[e] = 0.f;
+  for (int v = tid; v < nvec; v += MOE_THREADS) {
+    const half8 x8 = xv[v];
+#pragma unroll
+    for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e) {
+      if (e < p.n_experts) {
+        const half8 w8 = *reinterpret_cast<const half8*>(p.Wr + (size_t)e * p.rows.n + (size_t)v * 8);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[e] += (float)w8[c] * (float)x8[c];
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e) {
+    const float t = af_wave_sum(acc[e]);
+    if (lane == 0) s_part[wave][e] = t;
+  }
+  __syncthreads();
+  if (tid != 0) return;
+  float logit[AF_MOE_MAX_EXPERTS];
+  for (int e = 0; e < p.n_experts; ++e) {
+    float t = 0.f;
+    for (int w = 0; w < MOE_THREADS / AF_WAVE; ++w) t += s_part[w][e];
+    logit[e] = t;
+    p.logits[e] = t;
+  }
+  int chosen[AF_MOE_MAX_TOP];
+  float z[AF_MOE_MAX_TOP];
+  unsigned taken = 0;
+  for (int s = 0; s < p.top; ++s) {  // largest remaining logit, ties to the lower expert
+    int best = -1;
+    for (int e = 0; e < p.n_experts; ++e)
+      if (!((taken >> e) & 1u) && (best < 0 || logit[e] > logit[best])) best = e;
+    taken |= 1u << best;
+    chosen[s] = best;
+    z[s] = logit[best];
+  }
+  float den = 0.f;
+  for (int s = 0; s < p.top; ++s) {
+    z[s] = expf(z[s] - logit[chosen[0]]);
+    den += z[s];
+  }
+  for (int s = 0; s < p.top; ++s) {
+    p.experts[s] = chosen[s];
+    p.weights[s] = z[s] / den;
+  }
+}
+
+extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af_moe_weights* w,
+                                   const void* hidden_in, void* hidden_out, void* k_cache,
+                                   void* v_cache, int kv_len, int kv_cap, int pos,
+                                   const af_select_cfg* sel, const af_moe_sets* sets,
+                                   const af_moe_route* route) {
+  if (!ctx || !mcfg || !w || !hidden_in || !hidden_out || !k_cache || !v_cache || !sel || !route)
+    return AF_ENULL;
+  const af_layer_cfg* cfg = &mcfg->base;
+  int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
+  if (rc) return rc;
+  if (cfg->weight_kind != AF_W_F16) return AF_EINVAL;
+  if (mcfg->n_experts < 1 || mcfg->n_experts > AF_MOE_MAX_EXPERTS) return AF_EINVAL;
+  if (mcfg->top < 1 || mcfg->top > AF_MOE_MAX_TOP || mcfg->top > mcfg->n_experts) return AF_EINVAL;
+  if (sel->reuse_mask & 15u) return AF_EINVAL;
+  if (!w->Wqkv || !w->Wo || !w->g_attn_norm || !w->g_ffn_norm || !w->Wr || !w->Wgateup || !w->Wdown)
+    return AF_ENULL;
+  if (!route->experts || !route->weights || !route->logits) return AF_ENULL;
+  const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim, top = mcfg->top;
+  const int qdim = cfg->n_heads * hd, qkv_out = (cfg->n_heads + 2 * cfg->n_kv_heads) * hd;
+  if ((long long)top * 2 * f > ctx->max_out || (long long)top * f > ctx->max_in) return AF_EWORKSPACE;
+  const bool selects = sel->mode != AF_SEL_DENSE;
+  const bool write_sets = selects && !(sel->flags & AF_SEL_SKIP_SETS);
+  if (write_sets) {
+    if (!sets) return AF_ENULL;
+    for (int p = 0; p < 3 + top; ++p)
+      if (!sets->idx[p] || !sets->count[p]) return AF_ENULL;
+  }
+  half_t* act[7];
+  for (int i = 0; i < 7; ++i) act[i] = (half_t*)(ctx->ws + ctx->lay.act[i]);
+  half_t *x0 = act[0], *qkv = act[1], *attn = act[2], *hmid = act[3], *x2 = act[4], *gu = act[5],
+         *x3 = act[6];
+  const half_t* h_in = (const half_t*)hidden_in;
+  half_t* h_out = (half_t*)hidden_out;
+
+  // GEMV at selection point `point` (its k / threshold come from sel slot `cfg_p`)
+  auto gemv = [&](int point, int cfg_p, af_gemv_args& a, int producer, const half_t* src_v,
+                  const half_t* gain, half_t* x) -> int {
+    a.y_kind = AF_F16;
+    af_row_src& r = a.rows;
+    r.n = a.in;
+    r.eps = cfg->rms_eps;
+    r.pro = producer;
+    r.src = src_v;
+    r.gain = gain;
+    r.x_out = x;
+    if (selects) {
+      r.sel = sel->mode;
+      r.k = sel->k[cfg_p];
+      r.t = sel->t[cfg_p];
+      if (write_sets) {
+        r.idx_out = sets->idx[point];
+        r.count_out = sets->count[point];
+      }
+    } else {
+      r.sel = AF_ROWS_GIVEN;
+      r.idx = nullptr;
+      r.nidx_host = a.in;
+    }
+    return af_launch_gemv_f16(ctx, a);
+  };
+
+  {
+    af_gemv_args a{};
+    a.W = w->Wqkv; a.in = d; a.out = qkv_out; a.ld = qkv_out; a.y = qkv;
+    if ((rc = gemv(0, 0, a, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0))) return rc;
+  }
+  if ((rc = launch_attention(ctx, cfg, qkv, k_cache, v_cache, kv_len, kv_cap, pos, attn))) return rc;
+  {
+    af_gemv_args a{};
+    a.W = w->Wo; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;
+    if ((rc = gemv(1, 1, a, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
+  }
+  {
+    RouterParams rp{};
+    rp.rows.pro = AF_PRO_RMSNORM;
+    rp.rows.src = hmid;
+    rp.rows.gain = (const half_t*)w->g_ffn_norm;
+    rp.rows.eps = cfg->rms_eps;
+    rp.rows.n = d;
+    rp.Wr = (const half_t*)w->Wr;
+    rp.n_experts = mcfg->n_experts;
+    rp.top = top;
+    rp.experts = route->experts;
+    rp.weights = route->weights;
+    rp.logits = route->logits;
+    static bool attr_done = false;
+    if (!attr_done) {
+      attr_done = true;
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(moe_router_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * AF_MAX_N);
+    }
+    hipLaunchKernelGGL(moe_router_kernel, dim3(1), dim3(MOE_THREADS), af_align((size_t)d * 2, 16),
+                       ctx->stream, rp);
+    AF_LAUNCH_CHECK();
+  }
+  {
+    af_gemv_args a{};
+    a.W = w->Wgateup; a.in = d; a.out = top * 2 * f; a.ld = 2 * f; a.y = gu;
+    a.w_sel = route->experts; a.w_stride = (long long)d * 2 * f; a.n_slots = top;
+    if ((rc = gemv(2, 2, a, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2))) return rc;
+  }
+  for (int s = 0; s < top; ++s) {
+    af_gemv_args a{};
+    a.W = w->Wdown; a.in = f; a.out = d; a.ld = d; a.y = h_out;
+    a.residual = s == 0 ? hmid : h_out;
+    a.w_sel = route->experts + s; a.w_stride = (long long)f * d; a.n_slots = 1;
+    a.y_scale = route->weights + s;
+    if ((rc = gemv(3 + s, 3, a, AF_PRO_SILUMUL, gu + (size_t)s * 2 * f, nullptr, x3 + (size_t)s * f)))
+      return rc;
   }
   return AF_OK;
 }

@@ -146,3 +146,67 @@ class DeviceStack:
                               self.v_ptrs, kv_len, self.kv_cap, pos, sel, group, reuse_points,
                               self.sets_array)
         return out
+
+
+class DeviceMoeLayer:
+    """Packed weights and buffers of one mixture-of-experts block.  `host` holds the
+    attention-side matrices, g_attn, g_ffn, the router Wr [E][d] and per-expert lists Wgate,
+    Wup [ffn][d], Wdown [d][ffn] (fp16 NumPy arrays or torch tensors)."""
+
+    def __init__(self, ctx: B.Context, shape, host: dict, top: int = 2):
+        self.ctx, self.shape, self.top = ctx, shape, top
+        d, f, hd, E = shape.d_model, shape.d_ffn, shape.head_dim, shape.n_experts
+        nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
+        dev = ctx.device
+        up = lambda a: (a.to(dev).contiguous() if torch.is_tensor(a)
+                        else torch.from_numpy(np.ascontiguousarray(a)).to(dev))
+
+        def pack_into(parts, Wt):
+            col = 0
+            for p in parts:
+                Wd = up(p)
+                torch.cuda.current_stream().synchronize()
+                ctx.pack_inmajor_f16(Wd, Wt, col0=col)
+                ctx.synchronize()
+                col += p.shape[0]
+                del Wd
+
+        self.Wqkv = torch.empty((d, nq + 2 * nkv), dtype=torch.float16, device=dev)
+        pack_into([host["Wq"], host["Wk"], host["Wv"]], self.Wqkv)
+        self.Wo = torch.empty((nq, d), dtype=torch.float16, device=dev)
+        pack_into([host["Wo"]], self.Wo)
+        self.Wgateup = torch.empty((E, d, 2 * f), dtype=torch.float16, device=dev)
+        self.Wdown = torch.empty((E, f, d), dtype=torch.float16, device=dev)
+        for e in range(E):
+            pack_into([host["Wgate"][e], host["Wup"][e]], self.Wgateup[e])
+            pack_into([host["Wdown"][e]], self.Wdown[e])
+        self.Wr = up(host["Wr"])
+        self.g_attn, self.g_ffn = up(host["g_attn"]), up(host["g_ffn"])
+        self.cfg = B.MoeCfg(layer_cfg(shape), E, top)
+        widths = (d, nq, d) + (f,) * top
+        self.widths = widths
+        self.idx = [torch.zeros(n, dtype=torch.int32, device=dev) for n in widths]
+        self.count = [torch.zeros(1, dtype=torch.int32, device=dev) for _ in widths]
+        self.experts = torch.zeros(top, dtype=torch.int32, device=dev)
+        self.weights = torch.zeros(top, dtype=torch.float32, device=dev)
+        self.logits = torch.zeros(E, dtype=torch.float32, device=dev)
+        torch.cuda.current_stream().synchronize()
+
+    def weights_struct(self) -> B.MoeWeights:
+        p = lambda t: t.data_ptr()
+        return B.MoeWeights(p(self.Wqkv), p(self.Wo), p(self.g_attn), p(self.g_ffn), p(self.Wr),
+                            p(self.Wgateup), p(self.Wdown))
+
+    def sets_struct(self) -> B.MoeSets:
+        s = B.MoeSets()
+        for p in range(len(self.widths)):
+            s.idx[p] = self.idx[p].data_ptr()
+            s.count[p] = self.count[p].data_ptr()
+        return s
+
+    def route_struct(self) -> B.MoeRoute:
+        return B.MoeRoute(self.experts.data_ptr(), self.weights.data_ptr(), self.logits.data_ptr())
+
+    def run(self, hidden_in, hidden_out, K, V, kv_len: int, kv_cap: int, pos: int, sel: B.SelectCfg):
+        self.ctx.decode_moe_layer(self.cfg, self.weights_struct(), hidden_in, hidden_out, K, V, kv_len,
+                                  kv_cap, pos, sel, self.sets_struct(), self.route_struct())

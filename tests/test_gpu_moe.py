@@ -1,0 +1,133 @@
+"""GPU parity: af_decode_moe_layer against the oracle's mixture-of-experts block.
+
+The router decides integers from fp32 logits; the oracle's logits are fp64.  The expert
+choice is compared where the oracle's margin between the last chosen and the first rejected
+logit is far above fp32 rounding (always the case for the seeded inputs used here; asserted),
+the index sets as in the dense layer tests."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import activeflow_oracle as O
+from paper_2504_08378_amd import binding as B
+from paper_2504_08378_amd import model as M
+from gpu_util import ctx, to_dev, to_host  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+KV_LEN, KV_CAP = 37, 48
+
+
+def _setup(shape_name, seed):
+    shape = S.MODEL_SHAPES[shape_name]
+    w = S.moe_layer_weights(seed, shape, 0)
+    K, V = S.kv_cache(seed, shape.n_kv_heads, KV_CAP, shape.head_dim, KV_LEN, shape.name, 0)
+    h = S.activation(seed, S.channel_scales(seed, shape.d_model, shape.name), "hidden", 0)
+    cfg = O.LayerCfg(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn)
+    widths = (shape.d_model, shape.n_heads * shape.head_dim, shape.d_model, shape.d_ffn)
+    return shape, cfg, w, K, V, h, widths
+
+
+def _margin_ok(tr):
+    z = np.sort(tr.logits)[::-1]
+    top = len(tr.experts)
+    gaps = np.abs(np.diff(z[: top + 1]))
+    return gaps.min() > 1e-4 * max(1.0, np.abs(z).max())
+
+
+def _sets_close(got, ref, x_ref):
+    if np.array_equal(got, ref):
+        return True
+    key = (np.asarray(x_ref).view(np.uint16) & 0x7FFF).astype(np.int64)
+    thr = key[ref].min()
+    diff = np.setxor1d(got, ref)
+    return len(got) == len(ref) and np.all(np.abs(key[diff] - thr) <= 2)
+
+
+@pytest.mark.parametrize("sp", [50, 70])
+def test_moe_layer_topk(ctx, sp):
+    shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 11)
+    ks = tuple(O.keep_count(n, sp) for n in widths)
+    tr = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_TOPK, ks))
+    assert _margin_ok(tr)
+    lay = M.DeviceMoeLayer(ctx, shape, w)
+    Kd, Vd = to_dev(K), to_dev(V)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    lay.run(hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
+    ctx.synchronize()
+    assert to_host(lay.experts).tolist() == tr.experts.tolist()
+    assert np.allclose(to_host(lay.weights), tr.weights, rtol=1e-4)
+    assert np.allclose(to_host(lay.logits), tr.logits, rtol=1e-3, atol=1e-3)
+    d, f = shape.d_model, shape.d_ffn
+    assert O.rel_err(to_host(ctx.layer_tap(3, d)), tr.h_mid, 1.0) <= TOL
+    same = True
+    for p in range(3):
+        got = to_host(lay.idx[p])[: ks[p]]
+        assert _sets_close(got, tr.idx[p], tr.x[p]), p
+        same &= np.array_equal(got, tr.idx[p])
+    gu = to_host(ctx.layer_tap(5, 4 * f)); xd = to_host(ctx.layer_tap(6, 2 * f))
+    for s in range(2):
+        got = to_host(lay.idx[3 + s])[: ks[3]]
+        assert _sets_close(got, tr.idx_down[s], tr.x_down[s]), s
+        same &= np.array_equal(got, tr.idx_down[s])
+        assert O.rel_err(gu[s * 2 * f: (s + 1) * 2 * f], tr.gateup[s * 2 * f: (s + 1) * 2 * f], 1.0) <= (TOL if same else 5e-2)
+        assert O.rel_err(xd[s * f: (s + 1) * f], tr.x_down[s], 1.0) <= (TOL if same else 5e-2)
+    assert np.array_equal(to_host(Kd)[:, KV_LEN], tr.k_new)
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
+
+
+def test_moe_layer_dense_threshold_and_skip_sets(ctx):
+    shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 12)
+    lay = M.DeviceMoeLayer(ctx, shape, w)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    dense = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_DENSE))
+    assert _margin_ok(dense)
+    lay.run(hin, hout, to_dev(K), to_dev(V), KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_DENSE))
+    ctx.synchronize()
+    assert to_host(lay.experts).tolist() == dense.experts.tolist()
+    assert O.rel_err(to_host(hout), dense.hidden, 1.0) <= TOL
+    # thresholds in gaps of the magnitudes along the threshold-mode chain (point 3 serves both slots:
+    # its threshold sits in a gap of the pooled magnitudes of the two slots)
+    ts = [0.0] * 4
+    for p in range(4):
+        tr = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_THRESHOLD, t=tuple(ts)))
+        x = tr.x[p] if p < 3 else np.concatenate(tr.x_down)
+        m = np.sort(np.abs(x.astype(np.float64)))
+        lo = len(m) // 3
+        j = lo + int(np.argmax(np.diff(m)[lo: 2 * len(m) // 3]))
+        ts[p] = float(np.float32((m[j] + m[j + 1]) / 2))
+    tr = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_THRESHOLD, t=tuple(ts)))
+    assert _margin_ok(tr)
+    for flags in (0, B.AF_SEL_SKIP_SETS):
+        for p in range(5):
+            lay.count[p].fill_(-7)
+        lay.run(hin, hout, to_dev(K), to_dev(V), KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_THRESHOLD, t=ts, flags=flags))
+        ctx.synchronize()
+        assert to_host(lay.experts).tolist() == tr.experts.tolist()
+        same = True
+        if flags == 0:
+            for p in range(3):
+                same &= np.array_equal(to_host(lay.idx[p])[: int(lay.count[p].item())], tr.idx[p])
+            for s in range(2):
+                same &= np.array_equal(to_host(lay.idx[3 + s])[: int(lay.count[3 + s].item())], tr.idx_down[s])
+        else:
+            assert all(int(lay.count[p].item()) == -7 for p in range(5))
+        assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2), flags
+
+
+def test_moe_argument_errors(ctx):
+    shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 11)
+    lay = M.DeviceMoeLayer(ctx, shape, w)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    Kd, Vd = to_dev(K), to_dev(V)
+    ks = tuple(O.keep_count(n, 50) for n in widths)
+    with pytest.raises(B.AfError):
+        lay.run(hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=1))
+    bad = B.MoeCfg(lay.cfg.base, 99, 2)
+    with pytest.raises(B.AfError):
+        ctx.decode_moe_layer(bad, lay.weights_struct(), hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN,
+                             M.select_cfg(B.AF_SEL_TOPK, ks), lay.sets_struct(), lay.route_struct())
+    with pytest.raises(B.AfError):
+        ctx.decode_moe_layer(lay.cfg, lay.weights_struct(), hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN,
+                             M.select_cfg(B.AF_SEL_TOPK, ks), lay.sets_struct(), B.MoeRoute())
