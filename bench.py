@@ -116,6 +116,113 @@ def union_bench(args, S, B, torch, np) -> int:
     return 0
 
 
+def moe_bench(args, S, B, M, torch, np) -> int:
+    """--shape mixtral: decoder blocks with a mixture-of-experts feed-forward half (8 experts,
+    top-2).  Like the paper's technique evaluation it runs a slice of the model (8 layers by
+    default); tokens/s is the rate of that slice."""
+    shape = S.MODEL_SHAPES[args.shape]
+    L = args.layers or 8
+    sp, top = args.sparsity, 2
+    kv_len, kv_cap = args.kv_len, args.kv_len + 16
+    d, f = shape.d_model, shape.d_ffn
+    widths = (d, shape.n_heads * shape.head_dim, d, f)
+    ks = tuple(keep_count(n, sp) for n in widths)
+    ctx = B.Context(0)
+    t_build = time.time()
+    layers, kv = [], []
+    for l in range(L):
+        w = S.device_moe_layer_weights(0, shape, l)
+        layers.append(M.DeviceMoeLayer(ctx, shape, w, top))
+        kv.append(S.device_kv_cache(0, shape, l, kv_cap, kv_len))
+        del w
+    hin = torch.from_numpy(S.activation(0, S.channel_scales(0, d, shape.name), "hidden", 0)).cuda()
+    bufs = [torch.zeros_like(hin), torch.zeros_like(hin)]
+    torch.cuda.synchronize()
+    t_build = time.time() - t_build
+    sel = M.select_cfg(B.AF_SEL_TOPK, ks)
+
+    def run():
+        cur = hin
+        for l in range(L):
+            layers[l].run(cur, bufs[l & 1], kv[l][0], kv[l][1], kv_len, kv_cap, kv_len, sel)
+            cur = bufs[l & 1]
+
+    run()
+    ctx.synchronize()
+    experts = [layers[l].experts.cpu().tolist() for l in range(L)]
+    ctx.capture_begin()
+    run()
+    graph = ctx.capture_end()
+    for _ in range(args.warmup):
+        ctx.graph_launch(graph)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.graph_launch(graph)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tok_s = args.steps / dt
+    per_layer = (ks[0] * shape.qkv_out + ks[1] * d + ks[2] * top * 2 * f + top * ks[3] * d) * 2
+    active_bytes = per_layer * L
+
+    # dominant kernel: gate|up of the two chosen experts in one launch (rmsnorm + top-k + GEMV
+    # over device-selected matrices), rotating through the layers' expert banks
+    h2 = torch.from_numpy(S.activation(0, S.channel_scales(0, d, "roof"), "roof", 0)).cuda()
+    y2 = torch.empty(top * 2 * f, dtype=torch.float16, device="cuda")
+    x2 = torch.empty(d, dtype=torch.float16, device="cuda")
+    idx2 = torch.empty(d, dtype=torch.int32, device="cuda"); cnt2 = torch.empty(1, dtype=torch.int32, device="cuda")
+    pairs = [torch.tensor([(2 * i) % shape.n_experts, (2 * i + 1) % shape.n_experts], dtype=torch.int32, device="cuda")
+             for i in range(4)]
+    torch.cuda.synchronize()
+
+    def gateup(l, i):
+        lay = layers[l]
+        ctx.select_gemv_experts_f16(lay.Wgateup, pairs[i % 4], top, h2, producer=B.AF_PRO_RMSNORM,
+                                    gain=lay.g_ffn, eps=1e-5, sel_mode=B.AF_SEL_TOPK, k=ks[2], x_out=x2,
+                                    idx_out=idx2, count_out=cnt2, y=y2)
+
+    for l in range(L):
+        gateup(l, l)
+    ctx.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 4
+    e0.record(ctx.stream)
+    for r in range(reps):
+        for l in range(L):
+            gateup(l, r)
+    e1.record(ctx.stream)
+    ctx.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * L)
+    alg = ks[2] * (top * 2 * f * 2 + 6) + top * 2 * f * 2 + 2 * d * 2
+    achieved = alg / (us * 1e-6) / 1e9
+    out = {
+        "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+        "value": round(tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{args.shape}-shape mixture-of-experts blocks ({shape.n_experts} experts, top-{top}), "
+                               f"{L} layers, batch-1 decode, f16 weights, {sp}% sparsity at qkv/o/gate-up/down, "
+                               f"{kv_len}-token KV cache", "layers": L, "d_model": d, "d_ffn": f, "k": list(ks),
+                   "graph": True, "experts_chosen_layer0": experts[0]},
+        "active_weight_bytes_per_token": int(active_bytes),
+        "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
+        "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "ms_per_layer": round(dt / args.steps * 1e3 / L, 4),
+        "build_s": round(t_build, 1),
+        "roofline": {"bound": "hbm", "kernel": "gemv_f16_kernel<64, 8, 16> (gate|up of both chosen experts: rmsnorm + top-k + gathered GEMV)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_launch": alg,
+                     "us_per_launch": round(us, 3), "launches": reps * L},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    ctx.graph_destroy(graph)
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,6 +268,8 @@ def main() -> int:
 
     if args.union:
         return union_bench(args, S, B, torch, np)
+    if S.MODEL_SHAPES[args.shape].n_experts:
+        return moe_bench(args, S, B, M, torch, np)
     if args.overlap and args.select != "topk":
         print("bench.py: --overlap compares top-k sets; use it with --select topk", file=sys.stderr)
         return 2

@@ -141,6 +141,19 @@ int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, int
                        float t, void* x_out, int32_t* idx_out, int32_t* count_out, void* y,
                        int y_kind, const void* residual_f16);
 
+/* The same launch over matrices picked on the device (mixture of experts): the out columns
+ * are n_slots equal slots; slot s multiplies by the in-major matrix that starts
+ * expert_sel[s] * expert_stride elements behind Wt_all (leading dimension ld >= out/n_slots);
+ * expert_sel is device memory (written by the router), so no host round trip is needed.
+ * All slots share the input vector and its selection.  y_scale (device, one float, or NULL)
+ * multiplies the product before the residual is added.  (out / n_slots) % 8 == 0. */
+int af_select_gemv_experts_f16(af_ctx* ctx, const void* Wt_all, const int32_t* expert_sel,
+                               int n_slots, long long expert_stride, const float* y_scale, int in,
+                               int out, int ld, int producer, const void* src_f16,
+                               const void* gain_f16, float eps, int sel_mode, int k, float t,
+                               void* x_out, int32_t* idx_out, int32_t* count_out, void* y,
+                               int y_kind, const void* residual_f16);
+
 /* ---- small-batch union GEMV (extension of operation C to B tokens) ----------------------
  * Each of the B <= AF_MAX_BATCH tokens has its own index set idx_b[b][0..k); the kernel
  * reads every row of the union once and applies each token's mask:

@@ -30,7 +30,7 @@ EXPORTS = [
     "af_decode_layer", "af_decode_stack", "af_layer_tap", "af_capture_begin", "af_capture_end",
     "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
     "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
-    "af_decode_moe_layer",
+    "af_decode_moe_layer", "af_select_gemv_experts_f16",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -125,6 +125,8 @@ def lib() -> C.CDLL:
         "af_calib_accumulate": (i, [vp, vp, i, vp]),
         "af_calib_accumulate_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(vp)]),
         "af_calib_thresholds": (i, [vp, vp, C.POINTER(C.c_int), i, vp]),
+        "af_select_gemv_experts_f16": (i, [vp, vp, vp, i, C.c_longlong, vp, i, i, i, i, vp, vp, f, i, i, f,
+                                           vp, vp, vp, vp, i, vp]),
         "af_decode_moe_layer": (i, [vp, C.POINTER(MoeCfg), C.POINTER(MoeWeights), vp, vp, vp, vp,
                                     i, i, i, C.POINTER(SelectCfg), C.POINTER(MoeSets),
                                     C.POINTER(MoeRoute)]),
@@ -357,6 +359,24 @@ class Context:
             self._h, C.byref(cfg), w_array, n_layers, _ptr(hidden_in, torch.float16, "hidden_in"),
             _ptr(hidden_out, torch.float16, "hidden_out"), k_ptrs, v_ptrs, kv_len, kv_cap, pos,
             sel_arr, n_sel, group, reuse_points, sets_array), "af_decode_stack")
+
+    def select_gemv_experts_f16(self, Wt_all, expert_sel, n_slots, src, producer=AF_PRO_NONE, gain=None,
+                                eps=1e-5, sel_mode=AF_SEL_TOPK, k=0, t=0.0, x_out=None, idx_out=None,
+                                count_out=None, y=None, y_kind=AF_F16, residual=None, y_scale=None):
+        """Wt_all [E][in][cols]: slot s of y uses expert expert_sel[s] (device int32)."""
+        E, n_in, cols = Wt_all.shape
+        out = cols * n_slots
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        _check(lib().af_select_gemv_experts_f16(
+            self._h, _ptr(Wt_all, torch.float16, "Wt_all"), _ptr(expert_sel, torch.int32, "expert_sel"),
+            n_slots, n_in * cols, _ptr(y_scale, torch.float32, "y_scale"), n_in, out, cols, producer,
+            _ptr(src, torch.float16, "src"), _ptr(gain, torch.float16, "gain"), float(eps), sel_mode,
+            int(k), float(t), _ptr(x_out, torch.float16, "x_out"), _ptr(idx_out, torch.int32, "idx_out"),
+            _ptr(count_out, torch.int32, "count_out"), _ptr(y, None, "y"), y_kind,
+            _ptr(residual, torch.float16, "residual")), "af_select_gemv_experts_f16")
+        return y
 
     def decode_moe_layer(self, cfg: MoeCfg, w: MoeWeights, hidden_in, hidden_out, k_cache, v_cache,
                          kv_len: int, kv_cap: int, pos: int, sel: SelectCfg, sets, route: MoeRoute):

@@ -387,7 +387,9 @@ extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
   return af_launch_gemv_f16(ctx, a);
 }
 
-extern "C" int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, int producer,
+static int select_gemv_any(af_ctx* ctx, const int32_t* expert_sel, int n_slots,
+                           long long expert_stride, const float* y_scale, const void* Wt, int in,
+                           int out, int ld, int producer,
                                   const void* src_f16, const void* gain_f16, float eps,
                                   int sel_mode, int k, float t, void* x_out, int32_t* idx_out,
                                   int32_t* count_out, void* y, int y_kind,
@@ -397,7 +399,9 @@ extern "C" int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
     return AF_EINVAL;
   if (producer == AF_PRO_RMSNORM && !gain_f16) return AF_ENULL;
   if (in <= 0 || out <= 0 || in > AF_MAX_N) return AF_EINVAL;
-  if (in % 8 || out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
+  if (expert_sel && (n_slots < 1 || out % n_slots)) return AF_EINVAL;
+  const int cols = expert_sel ? out / n_slots : out;  // columns of one matrix
+  if (in % 8 || cols % 8 || ld % 8 || ld < cols) return AF_ESHAPE;
   if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
   if (sel_mode != AF_SEL_TOPK && sel_mode != AF_SEL_THRESHOLD && sel_mode != AF_SEL_DENSE)
     return AF_EINVAL;
@@ -430,5 +434,31 @@ extern "C" int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
   a.y = y;
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;
+  a.w_sel = expert_sel;
+  a.n_slots = n_slots;
+  a.w_stride = expert_stride;
+  a.y_scale = y_scale;
   return af_launch_gemv_f16(ctx, a);
+}
+
+extern "C" int af_select_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld, int producer,
+                                  const void* src_f16, const void* gain_f16, float eps,
+                                  int sel_mode, int k, float t, void* x_out, int32_t* idx_out,
+                                  int32_t* count_out, void* y, int y_kind,
+                                  const void* residual_f16) {
+  return select_gemv_any(ctx, nullptr, 1, 0, nullptr, Wt, in, out, ld, producer, src_f16, gain_f16,
+                         eps, sel_mode, k, t, x_out, idx_out, count_out, y, y_kind, residual_f16);
+}
+
+extern "C" int af_select_gemv_experts_f16(af_ctx* ctx, const void* Wt_all, const int32_t* expert_sel,
+                                          int n_slots, long long expert_stride, const float* y_scale,
+                                          int in, int out, int ld, int producer, const void* src_f16,
+                                          const void* gain_f16, float eps, int sel_mode, int k,
+                                          float t, void* x_out, int32_t* idx_out, int32_t* count_out,
+                                          void* y, int y_kind, const void* residual_f16) {
+  if (!expert_sel) return AF_ENULL;
+  if (expert_stride < 0) return AF_EINVAL;
+  return select_gemv_any(ctx, expert_sel, n_slots, expert_stride, y_scale, Wt_all, in, out, ld,
+                         producer, src_f16, gain_f16, eps, sel_mode, k, t, x_out, idx_out, count_out,
+                         y, y_kind, residual_f16);
 }

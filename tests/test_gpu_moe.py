@@ -131,3 +131,37 @@ def test_moe_argument_errors(ctx):
     with pytest.raises(B.AfError):
         ctx.decode_moe_layer(lay.cfg, lay.weights_struct(), hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN,
                              M.select_cfg(B.AF_SEL_TOPK, ks), lay.sets_struct(), B.MoeRoute())
+
+
+@pytest.mark.parametrize("cols,n,E,slots", [(136, 64, 3, 2), (2752, 512, 4, 2), (520, 1000, 5, 3),
+                                            (28672, 256, 2, 2), (4096, 1376, 4, 1)])
+def test_expert_indexed_gemv(ctx, cols, n, E, slots):
+    """af_select_gemv_experts_f16: slot s of the output multiplies by the matrix of expert
+    sel[s]; widths that are not a multiple of the tile leave ragged slot edges."""
+    g = np.random.default_rng(cols + n)
+    Ws = [S.weight_matrix(cols + n, cols, n, "experts", e) for e in range(E)]
+    x = S.activation(cols, S.channel_scales(cols, n, "experts"), "experts", 0)
+    Wt_all = torch.empty((E, n, cols), dtype=torch.float16, device="cuda")
+    for e in range(E):
+        ctx.pack_inmajor_f16(to_dev(Ws[e]), Wt_all[e])
+    ctx.synchronize()
+    sel = g.choice(E, size=slots, replace=False).astype(np.int32)
+    k = n // 2
+    idx = O.select_topk(x, k)
+    io = torch.zeros(n, dtype=torch.int32, device="cuda"); co = torch.zeros(1, dtype=torch.int32, device="cuda")
+    y = ctx.select_gemv_experts_f16(Wt_all, to_dev(sel), slots, to_dev(x), sel_mode=B.AF_SEL_TOPK, k=k,
+                                    idx_out=io, count_out=co, y_kind=B.AF_F32)
+    ctx.synchronize()
+    assert np.array_equal(to_host(io)[:k], idx)
+    ref = np.concatenate([O.sparse_gemv(Ws[e], x, idx) for e in sel])
+    assert O.rel_err(to_host(y), ref) <= 1e-4
+    # scaled product added to a residual, threshold form without an index list
+    res = S.activation(7, S.channel_scales(7, cols * slots, "experts-res"), "experts-res", 0)
+    scale = np.array([0.375], np.float32)
+    t = float(np.sort(np.abs(x.astype(np.float64)))[n // 2])
+    y = ctx.select_gemv_experts_f16(Wt_all, to_dev(sel), slots, to_dev(x), sel_mode=B.AF_SEL_THRESHOLD, t=t,
+                                    residual=to_dev(res), y_scale=to_dev(scale))
+    ctx.synchronize()
+    idx_t = O.select_threshold(x, t)
+    ref = res.astype(np.float64) + 0.375 * np.concatenate([O.sparse_gemv(Ws[e], x, idx_t) for e in sel])
+    assert O.rel_err(to_host(y), ref) <= TOL
