@@ -518,3 +518,106 @@ def rel_err(got, ref, floor_frac: float = 0.01) -> float:
     den = np.maximum(np.abs(ref), floor)
     den = np.where(den == 0, 1.0, den)
     return float(np.max(np.abs(got - ref) / den))
+
+
+# --------------------------------------------------------------------------
+# dynamic weight caching (Section 4.2) and the cost model (Section 4.3)
+# --------------------------------------------------------------------------
+class LfuCache:
+    """Least-frequently-used cache of weight channels of one tensor (Section 4.2,
+    "Dynamic LLM Weight Caching"): one usage counter per channel, all zero at the
+    start; the cache holds at most `capacity` channels.
+
+    One token (step): the needed channels found in the cache are hits; every needed
+    channel's counter goes up by one; then the missed channels, in ascending order,
+    try to enter: into a free slot if there is one, otherwise in place of the
+    least-used cached channel that this token does not need.
+
+    Readings.  (1) The text lets a newcomer in when its count is "higher" than the
+    least-used channel's, but its own worked example replaces channel 1 (count 1) by
+    channel 7 (count 1): the example decides, the test is >=.  (2) Among equally
+    little-used cached channels the lowest index leaves first.  (3) A channel the
+    current token needs is never the victim.  (4) The hit ratio of a token is
+    hits / needed channels, taken before anything enters."""
+
+    def __init__(self, n_channels: int, capacity: int, initial=()):
+        self.n, self.capacity = int(n_channels), int(capacity)
+        self.count = [0] * self.n
+        self.cached = set(int(c) for c in initial)
+        if len(self.cached) > self.capacity or any(not 0 <= c < self.n for c in self.cached):
+            raise ValueError("bad initial cache content")
+        self.tokens = self.needed = self.hits = self.evictions = 0
+
+    def step(self, idx):
+        """Returns (hits, loaded, evicted list) for one token's needed channels."""
+        need = sorted(set(int(j) for j in idx))
+        hit = [j for j in need if j in self.cached]
+        miss = [j for j in need if j not in self.cached]
+        for j in need:
+            self.count[j] += 1
+        evicted = []
+        for j in miss:
+            if len(self.cached) < self.capacity:
+                self.cached.add(j)
+                continue
+            victims = [c for c in self.cached if c not in need]
+            if not victims:
+                continue
+            m = min(victims, key=lambda c: (self.count[c], c))
+            if self.count[j] >= self.count[m]:
+                self.cached.remove(m)
+                self.cached.add(j)
+                evicted.append(m)
+        self.tokens += 1
+        self.needed += len(need)
+        self.hits += len(hit)
+        self.evictions += len(evicted)
+        return len(hit), len(miss), evicted
+
+
+def cost_model(sp, hr, si, bw_mem, bw_flash_small, bw_flash_large, S_l, N, M_cache, M_kv):
+    """Eq. 1-9 of Section 4.3 as printed (the prose around them names two terms wrongly;
+    the equations are taken).  Sizes in bytes, bandwidths in bytes/s, times in seconds.
+    Returns a dict with M_cl, M, T_load, T_comp, T_onload, T_preload, T_overlap, T_decode."""
+    M_cl = S_l * (1.0 - sp) * N                                   # Eq. 9
+    T_load = M_cl * (1.0 - hr) / bw_flash_small                   # Eq. 3
+    T_comp = M_cl / bw_mem                                        # Eq. 4
+    T_onload = S_l * (1.0 - sp) * (1.0 - hr) * (1.0 - si) / bw_flash_small   # Eq. 6
+    T_preload = M_cl * (1.0 - hr) / bw_flash_large                # Eq. 7
+    T_overlap = T_onload + max(T_preload, T_comp)                 # Eq. 5
+    return {"M_cl": M_cl, "M": M_cl + M_cache + M_kv,             # Eq. 8
+            "T_load": T_load, "T_comp": T_comp, "T_onload": T_onload, "T_preload": T_preload,
+            "T_overlap": T_overlap, "T_decode": T_load + T_overlap + T_comp}   # Eq. 1
+
+
+def plan_search(M_max, S_m, S_l, M_kv, si, bw_mem, bw_flash_small, bw_flash_large, hr_of_fraction,
+                n_max=64, min_gain=0.0):
+    """Greedy parameter search of Section 4.3 ("Preload-and-computation-balanced cross-layer
+    group search").  sp = 1 - M_max / S_m (clamped to [0, 1)); then N = 1, 2, ...: the group
+    takes M_cl (Eq. 9), the cache gets what the budget leaves, M_cache = M_max - M_cl - M_kv
+    (Eq. 2 and 8 with equality), its hit rate is hr_of_fraction(M_cache / (S_m (1 - sp))), a
+    caller-supplied curve (the paper measures it, Fig. "cache rate and load rate").  Stops
+    when the budget is exhausted, when T_preload <= T_comp, or when T_preload changed by less
+    than min_gain against the previous N.  Reading: the paper says the decode time is
+    minimised "recursively" over these steps; the candidate of lowest T_decode among the ones
+    visited is returned.  Returns (sp, N, M_cache, costs dict, visited list)."""
+    sp = min(max(1.0 - M_max / S_m, 0.0), 1.0 - 1e-12)
+    best, visited, prev = None, [], None
+    for N in range(1, n_max + 1):
+        M_cl = S_l * (1.0 - sp) * N
+        M_cache = M_max - M_cl - M_kv
+        if M_cache < 0:
+            break
+        hr = hr_of_fraction(M_cache / (S_m * (1.0 - sp)))
+        c = cost_model(sp, hr, si, bw_mem, bw_flash_small, bw_flash_large, S_l, N, M_cache, M_kv)
+        visited.append((N, M_cache, hr, c))
+        if best is None or c["T_decode"] < best[3]["T_decode"]:
+            best = (N, M_cache, hr, c)
+        if c["T_preload"] <= c["T_comp"]:
+            break
+        if prev is not None and abs(prev - c["T_preload"]) < min_gain:
+            break
+        prev = c["T_preload"]
+    if best is None:
+        return sp, 0, 0.0, None, visited
+    return sp, best[0], best[1], best[3], visited
