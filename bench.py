@@ -239,6 +239,9 @@ def main() -> int:
                     help="threshold: per-operator thresholds calibrated for --sparsity on "
                          "--calib-tokens synthetic tokens, selection fused into the GEMVs")
     ap.add_argument("--calib-tokens", type=int, default=8)
+    ap.add_argument("--lfu-tokens", type=int, default=0, metavar="T",
+                    help="also decode T synthetic tokens (untimed) and feed the index sets of layer 0 and "
+                         "the middle layer to the weight-cache simulator at cache fractions 25/50/75 %%")
     ap.add_argument("--kv-len", type=int, default=512)
     ap.add_argument("--overlap", action="store_true",
                     help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
@@ -550,6 +553,40 @@ def main() -> int:
                    "layer1": per_layer[1] if L > 1 else None,
                    "last_follower": per_layer[L - 1] if (L - 1) % args.group else per_layer[L - 2]}
 
+    lfu = None
+    if args.lfu_tokens > 0 and args.select == "topk":
+        # Section 4.2 on the index streams of the hot path: per tensor, an LFU cache of a fraction
+        # of its channels; hit ratio = needed channels found cached, averaged over the tokens after
+        # the first (the cache starts with the lowest-numbered channels, an arbitrary content)
+        watch = sorted({0, L // 2})
+        fracs = (0.25, 0.5, 0.75)
+        caches = {(l, p, fr): B.LfuCache(widths[p], int(widths[p] * fr), list(range(int(widths[p] * fr))))
+                  for l in watch for p in range(4) for fr in fracs}
+        hit = {k: [0, 0] for k in caches}
+        scales = S.channel_scales(0, shape.d_model, shape.name)
+        t_sim, n_sim = 0.0, 0
+        for tok in range(1, args.lfu_tokens + 1):
+            cur = torch.from_numpy(S.activation(0, scales, "hidden", tok)).cuda()
+            torch.cuda.synchronize()
+            st.run(cur, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks))
+            ctx.synchronize()
+            for l in watch:
+                for p in range(4):
+                    idx = st.sets[l].fetch(p, ks[p]).tolist()
+                    for fr in fracs:
+                        t1 = time.perf_counter()
+                        h, ld, _ = caches[(l, p, fr)].step(idx)
+                        t_sim += time.perf_counter() - t1
+                        n_sim += 1
+                        if tok > 1:
+                            hit[(l, p, fr)][0] += h
+                            hit[(l, p, fr)][1] += h + ld
+        lfu = {"tokens": args.lfu_tokens, "points": ["qkv", "o", "gateup", "down"],
+               "hit_ratio": {f"layer{l}@{int(fr * 100)}%": [round(hit[(l, p, fr)][0] / max(1, hit[(l, p, fr)][1]), 4)
+                                                            for p in range(4)] for l in watch for fr in fracs},
+               "keep_fraction": round(1 - sp / 100, 2),
+               "simulator_us_per_step": round(t_sim / max(1, n_sim) * 1e6, 1)}
+
     wl = f"{args.shape}-shape decoder stack, {L} layers, batch-1 decode, {args.weights} weights, " \
          f"{sp}% sparsity at qkv/o/gate-up/down, {kv_len}-token KV cache"
     if keep_frac is not None:
@@ -573,6 +610,8 @@ def main() -> int:
     }
     if keep_frac is not None:
         out["config"]["kept_fraction_by_point"] = keep_frac
+    if lfu is not None:
+        out["lfu_cache"] = lfu
     if overlap is not None:
         out["overlap_reused_vs_own"] = overlap
     print(json.dumps(out))

@@ -298,6 +298,64 @@ int af_calib_accumulate_layer(af_ctx* ctx, const af_layer_cfg* cfg, uint32_t* co
 int af_calib_thresholds(af_ctx* ctx, const uint32_t* hist, const int* sparsity_pct, int n_levels,
                         float* t_out);
 
+/* ---- host-side tools (host memory only; no GPU work) --------------------------------------
+ * Dynamic weight caching, Section 4.2: one usage counter per channel of a tensor (zero at the
+ * start), a cache of at most `capacity` channels.  af_lfu_step takes the ascending, unique
+ * channels one token needs: those found in the cache are hits; every needed channel's counter
+ * goes up; then the missed channels, in ascending order, enter a free slot, or replace the
+ * least-used cached channel the token does not need (ties: lower channel) when their own
+ * count is >= that channel's (the paper's worked example fixes >= over the ">" of its text);
+ * otherwise they pass by uncached.  evicted (capacity entries, may be NULL) receives the
+ * channels that left; hits / loaded / n_evicted may be NULL. */
+typedef struct af_lfu af_lfu;
+int af_lfu_create(af_lfu** out, int n_channels, int capacity, const int32_t* initial, int n_initial);
+int af_lfu_destroy(af_lfu* c);
+int af_lfu_step(af_lfu* c, const int32_t* idx, int nidx, int* hits, int* loaded, int32_t* evicted,
+                int* n_evicted);
+int af_lfu_stats(const af_lfu* c, long long* tokens, long long* needed, long long* hits,
+                 long long* evictions);
+int af_lfu_cached(const af_lfu* c, int32_t* channels /* capacity entries or NULL */, int* n_cached);
+
+/* Cost model, Section 4.3, Eq. 1-9 as printed (bytes, bytes/s, seconds):
+ *   M_cl = S_l (1-sp) N;  T_load = M_cl (1-hr) / bw_flash_small;  T_comp = M_cl / bw_mem;
+ *   T_onload = S_l (1-sp)(1-hr)(1-si) / bw_flash_small;  T_preload = M_cl (1-hr) / bw_flash_large;
+ *   T_overlap = T_onload + max(T_preload, T_comp);  T_decode = T_load + T_overlap + T_comp;
+ *   M = M_cl + M_cache + M_kv.
+ * "flash" is whatever tier lies below the memory the GEMVs stream from (on an MI355X: host
+ * memory behind the HBM). */
+typedef struct {
+  double sp, hr, si;
+  double bw_mem, bw_flash_small, bw_flash_large;
+  double S_l, N, M_cache, M_kv;
+} af_cost_in;
+typedef struct {
+  double M_cl, M, T_load, T_comp, T_onload, T_preload, T_overlap, T_decode;
+} af_cost_out;
+int af_cost_eval(const af_cost_in* in, af_cost_out* out);
+
+/* Greedy search of Section 4.3: sp = 1 - M_max / S_m (clamped to [0, 1)); N = 1, 2, ... with
+ * the cache taking what the budget leaves (M_cache = M_max - M_cl - M_kv) and its hit rate read
+ * off the caller's curve at M_cache / (S_m (1-sp)) (n_hr points, ascending fractions, linear in
+ * between, flat outside); stops when the budget is exhausted, when T_preload <= T_comp, or when
+ * T_preload changed by less than min_gain; returns the visited candidate of lowest T_decode
+ * (N == 0: none fits). */
+enum { AF_PLAN_MAX_HR = 64 };
+typedef struct {
+  double M_max, S_m, S_l, M_kv, si;
+  double bw_mem, bw_flash_small, bw_flash_large;
+  const double* hr_fraction;
+  const double* hr_value;
+  int n_hr, n_max;
+  double min_gain;
+} af_plan_in;
+typedef struct {
+  double sp;
+  int N, visited;
+  double M_cache, hr;
+  af_cost_out cost;
+} af_plan_out;
+int af_plan_search(const af_plan_in* in, af_plan_out* out);
+
 /* Measurement aid (the Eq. 4 memory-bandwidth term BW_mem of this device): one plain
  * streaming-read kernel over `bytes` of device memory at dev_ptr (16-byte aligned; bytes a
  * multiple of 16) with 16-byte loads, queued on the context's stream, in a grid of

@@ -31,6 +31,8 @@ EXPORTS = [
     "af_graph_launch", "af_graph_destroy", "af_probe_sink_floats", "af_probe_stream_read",
     "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
     "af_decode_moe_layer", "af_select_gemv_experts_f16",
+    "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
+    "af_cost_eval", "af_plan_search",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -77,6 +79,28 @@ class MoeSets(C.Structure):
 
 class MoeRoute(C.Structure):
     _fields_ = [("experts", C.c_void_p), ("weights", C.c_void_p), ("logits", C.c_void_p)]
+
+
+class CostIn(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("sp", "hr", "si", "bw_mem", "bw_flash_small", "bw_flash_large",
+                                          "S_l", "N", "M_cache", "M_kv")]
+
+
+class CostOut(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("M_cl", "M", "T_load", "T_comp", "T_onload", "T_preload",
+                                          "T_overlap", "T_decode")]
+
+
+class PlanIn(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("M_max", "S_m", "S_l", "M_kv", "si", "bw_mem", "bw_flash_small",
+                                          "bw_flash_large")] + \
+               [("hr_fraction", C.POINTER(C.c_double)), ("hr_value", C.POINTER(C.c_double)),
+                ("n_hr", C.c_int), ("n_max", C.c_int), ("min_gain", C.c_double)]
+
+
+class PlanOut(C.Structure):
+    _fields_ = [("sp", C.c_double), ("N", C.c_int), ("visited", C.c_int), ("M_cache", C.c_double),
+                ("hr", C.c_double), ("cost", CostOut)]
 
 
 _lib = None
@@ -127,6 +151,14 @@ def lib() -> C.CDLL:
         "af_calib_thresholds": (i, [vp, vp, C.POINTER(C.c_int), i, vp]),
         "af_select_gemv_experts_f16": (i, [vp, vp, vp, i, C.c_longlong, vp, i, i, i, i, vp, vp, f, i, i, f,
                                            vp, vp, vp, vp, i, vp]),
+        "af_lfu_create": (i, [C.POINTER(vp), i, i, C.POINTER(C.c_int32), i]),
+        "af_lfu_destroy": (i, [vp]),
+        "af_lfu_step": (i, [vp, C.POINTER(C.c_int32), i, C.POINTER(i), C.POINTER(i), C.POINTER(C.c_int32),
+                            C.POINTER(i)]),
+        "af_lfu_stats": (i, [vp] + [C.POINTER(C.c_longlong)] * 4),
+        "af_lfu_cached": (i, [vp, C.POINTER(C.c_int32), C.POINTER(i)]),
+        "af_cost_eval": (i, [C.POINTER(CostIn), C.POINTER(CostOut)]),
+        "af_plan_search": (i, [C.POINTER(PlanIn), C.POINTER(PlanOut)]),
         "af_decode_moe_layer": (i, [vp, C.POINTER(MoeCfg), C.POINTER(MoeWeights), vp, vp, vp, vp,
                                     i, i, i, C.POINTER(SelectCfg), C.POINTER(MoeSets),
                                     C.POINTER(MoeRoute)]),
@@ -442,3 +474,64 @@ class Context:
         _check(lib().af_probe_stream_read(self._h, C.c_void_p(_ptr(buf, torch.uint8).value + offset),
                                           nbytes, _ptr(sink, torch.float32), wgs_per_cu),
                "af_probe_stream_read")
+
+
+# ---- host-side tools (no GPU needed) -------------------------------------------------------
+class LfuCache:
+    """Dynamic weight-cache simulator (Section 4.2) on host memory."""
+
+    def __init__(self, n_channels: int, capacity: int, initial=()):
+        init = (C.c_int32 * max(1, len(initial)))(*[int(v) for v in initial])
+        h = C.c_void_p()
+        _check(lib().af_lfu_create(C.byref(h), n_channels, capacity, init, len(initial)), "af_lfu_create")
+        self._h, self.capacity = h, capacity
+        self._ev = (C.c_int32 * max(1, capacity))()
+
+    def step(self, idx):
+        """idx: ascending unique channels of one token.  Returns (hits, loaded, evicted list)."""
+        arr = (C.c_int32 * max(1, len(idx)))(*[int(v) for v in idx])
+        h, l, ne = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().af_lfu_step(self._h, arr, len(idx), C.byref(h), C.byref(l), self._ev, C.byref(ne)),
+               "af_lfu_step")
+        return h.value, l.value, list(self._ev[: ne.value])
+
+    def stats(self):
+        v = [C.c_longlong() for _ in range(4)]
+        _check(lib().af_lfu_stats(self._h, *[C.byref(x) for x in v]), "af_lfu_stats")
+        return dict(zip(("tokens", "needed", "hits", "evictions"), [x.value for x in v]))
+
+    def cached(self):
+        out = (C.c_int32 * max(1, self.capacity))()
+        n = C.c_int()
+        _check(lib().af_lfu_cached(self._h, out, C.byref(n)), "af_lfu_cached")
+        return list(out[: n.value])
+
+    def close(self):
+        if self._h:
+            lib().af_lfu_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def cost_eval(**kw) -> dict:
+    cin, out = CostIn(**kw), CostOut()
+    _check(lib().af_cost_eval(C.byref(cin), C.byref(out)), "af_cost_eval")
+    return {n: getattr(out, n) for n, _ in CostOut._fields_}
+
+
+def plan_search(M_max, S_m, S_l, M_kv, si, bw_mem, bw_flash_small, bw_flash_large, hr_points, n_max=64,
+                min_gain=0.0) -> dict:
+    """hr_points: [(cache fraction, hit rate), ...] with ascending fractions."""
+    fr = (C.c_double * len(hr_points))(*[float(p[0]) for p in hr_points])
+    hv = (C.c_double * len(hr_points))(*[float(p[1]) for p in hr_points])
+    pin = PlanIn(M_max, S_m, S_l, M_kv, si, bw_mem, bw_flash_small, bw_flash_large, fr, hv, len(hr_points),
+                 n_max, min_gain)
+    out = PlanOut()
+    _check(lib().af_plan_search(C.byref(pin), C.byref(out)), "af_plan_search")
+    return {"sp": out.sp, "N": out.N, "visited": out.visited, "M_cache": out.M_cache, "hr": out.hr,
+            "cost": {n: getattr(out.cost, n) for n, _ in CostOut._fields_}}
