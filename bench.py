@@ -127,12 +127,13 @@ def moe_bench(args, S, B, M, torch, np) -> int:
     d, f = shape.d_model, shape.d_ffn
     widths = (d, shape.n_heads * shape.head_dim, d, f)
     ks = tuple(keep_count(n, sp) for n in widths)
+    kind = {"f16": B.AF_W_F16, "q4": B.AF_W_Q4G32, "q4cl": B.AF_W_Q4CL}[args.weights]
     ctx = B.Context(0)
     t_build = time.time()
     layers, kv = [], []
     for l in range(L):
         w = S.device_moe_layer_weights(0, shape, l)
-        layers.append(M.DeviceMoeLayer(ctx, shape, w, top))
+        layers.append(M.DeviceMoeLayer(ctx, shape, w, top, kind))
         kv.append(S.device_kv_cache(0, shape, l, kv_cap, kv_len))
         del w
     hin = torch.from_numpy(S.activation(0, S.channel_scales(0, d, shape.name), "hidden", 0)).cuda()
@@ -164,8 +165,37 @@ def moe_bench(args, S, B, M, torch, np) -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     tok_s = args.steps / dt
-    per_layer = (ks[0] * shape.qkv_out + ks[1] * d + ks[2] * top * 2 * f + top * ks[3] * d) * 2
+    outs = (shape.qkv_out, d, top * 2 * f, d)
+    mult = (1, 1, 1, top)                                   # the down projection runs once per slot
+    bpw = 2.0 if kind == B.AF_W_F16 else 0.5
+    per_layer = sum(mult[p] * ks[p] * outs[p] for p in range(4)) * bpw
+    if kind == B.AF_W_Q4G32:
+        per_layer += sum(mult[p] * (widths[p] // 32) * outs[p] for p in range(4)) * 2
+    elif kind == B.AF_W_Q4CL:
+        per_layer += sum(mult[p] * ks[p] * (outs[p] // 32) for p in range(4)) * 2
     active_bytes = per_layer * L
+
+    roofline = None
+    if kind != B.AF_W_F16:
+        out = {
+            "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+            "value": round(tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "int4", "data": "synthetic",
+            "config": {"workload": f"{args.shape}-shape mixture-of-experts blocks ({shape.n_experts} experts, top-{top}), "
+                                   f"{L} layers, batch-1 decode, {args.weights} weights, {sp}% sparsity at "
+                                   f"qkv/o/gate-up/down, {kv_len}-token KV cache", "layers": L, "d_model": d,
+                       "d_ffn": f, "k": list(ks), "graph": True, "experts_chosen_layer0": experts[0]},
+            "active_weight_bytes_per_token": int(active_bytes),
+            "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
+            "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),
+            "ms_per_layer": round(dt / args.steps * 1e3 / L, 4), "build_s": round(t_build, 1),
+            "roofline": None, "cpu_baseline": None,
+        }
+        print(json.dumps(out))
+        ctx.graph_destroy(graph)
+        ctx.close()
+        return 0
 
     # dominant kernel: gate|up of the two chosen experts in one launch (rmsnorm + top-k + GEMV
     # over device-selected matrices), rotating through the layers' expert banks

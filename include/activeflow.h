@@ -238,15 +238,18 @@ int af_decode_stack(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
  * The experts are reached on the device (no host round trip): the call can be captured. */
 enum { AF_MOE_MAX_EXPERTS = 16, AF_MOE_MAX_TOP = 4 };
 typedef struct {
-  af_layer_cfg base; /* d_ffn: width of one expert; weight_kind must be AF_W_F16 */
+  af_layer_cfg base; /* d_ffn: width of one expert */
   int n_experts, top;
 } af_moe_cfg;
 /* Wqkv, Wo, g_*: as af_layer_weights.  Wr fp16 [n_experts][d] (one row per expert).
- * Wgateup fp16 [n_experts][d][2*ffn]: expert e's in-major gate|up matrix at element offset
- * e*d*2*ffn; Wdown fp16 [n_experts][ffn][d] likewise. */
+ * Wgateup [n_experts][d][2*ffn]: expert e's in-major gate|up matrix behind expert e-1's;
+ * Wdown [n_experts][ffn][d] likewise.  For 4-bit weight kinds W* are packed nibbles and S*
+ * their scales, every expert's matrix packed on its own (af_pack_q4_g32 / af_pack_q4_cl with
+ * ld = the matrix's own width) and the banks stored expert after expert; S* are NULL for fp16. */
 typedef struct {
   const void *Wqkv, *Wo, *g_attn_norm, *g_ffn_norm;
   const void *Wr, *Wgateup, *Wdown;
+  const void *Sqkv, *So, *Sgateup, *Sdown;
 } af_moe_weights;
 /* Index sets: points 0 qkv, 1 o, 2 gate/up (shared by the chosen experts), 3+s the down
  * projection of slot s.  Written unless sel->flags has AF_SEL_SKIP_SETS (then they may be

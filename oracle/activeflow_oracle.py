@@ -430,7 +430,7 @@ class MoeTrace(LayerTrace):
 
 
 def decode_moe_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int,
-                     sel: SelectCfg, top: int = 2) -> MoeTrace:
+                     sel: SelectCfg, top: int = 2, weights_q4=False) -> MoeTrace:
     """Decode step of a block whose feed-forward half is a sparse mixture of experts.
 
     The paper deploys Mixtral-8x7B with its method but gives no MoE-specific rule, so the
@@ -442,10 +442,11 @@ def decode_moe_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int
     one slot at a time, weighted by the router: h <- fp16(h + w_s * down_s(...)).
 
     w: the attention-side keys of decode_layer, g_ffn, Wr [E][d], and lists Wgate[e],
-    Wup[e] [ffn][d], Wdown[e] [d][ffn]."""
+    Wup[e] [ffn][d], Wdown[e] [d][ffn] (with weights_q4, every matrix but the router is a
+    (nib, scales) pair as in decode_layer)."""
     tr = MoeTrace()
     h0 = np.asarray(hidden, dtype=np.float16)
-    h1 = _attention_block(cfg, w, h0, K, V, kv_len, pos, sel, None, False, tr)
+    h1 = _attention_block(cfg, w, h0, K, V, kv_len, pos, sel, None, weights_q4, tr)
     x2 = round_f16(rmsnorm(h1, w["g_ffn"], cfg.rms_eps))
     experts, weights, logits = moe_route(x2, w["Wr"], top)
     i2 = _select(x2, P_GATEUP, sel, None)
@@ -453,12 +454,12 @@ def decode_moe_layer(cfg: LayerCfg, w: dict, hidden, K, V, kv_len: int, pos: int
     h = h1
     tr.x_down, tr.idx_down, tr.h_slots, gus = [], [], [], []
     for s, e in enumerate(experts):
-        g = sparse_gemv(w["Wgate"][e], x2, i2)
-        u = sparse_gemv(w["Wup"][e], x2, i2)
+        g = _linear(w["Wgate"][e], x2, i2, weights_q4)
+        u = _linear(w["Wup"][e], x2, i2, weights_q4)
         gu16 = round_f16(np.concatenate([g, u]))
         x3 = round_f16(silu(gu16[:f]) * gu16[f:].astype(np.float64))
         i3 = _select(x3, P_DOWN, sel, None)
-        h = round_f16(h.astype(np.float64) + weights[s] * sparse_gemv(w["Wdown"][e], x3, i3))
+        h = round_f16(h.astype(np.float64) + weights[s] * _linear(w["Wdown"][e], x3, i3, weights_q4))
         gus.append(gu16); tr.x_down.append(x3); tr.idx_down.append(i3); tr.h_slots.append(h)
     tr.x[2:] = [x2, tr.x_down[0]]
     tr.idx[2:] = [i2, tr.idx_down[0]]

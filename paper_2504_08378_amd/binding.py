@@ -70,7 +70,8 @@ class MoeCfg(C.Structure):
 
 class MoeWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
-                ("Wqkv", "Wo", "g_attn_norm", "g_ffn_norm", "Wr", "Wgateup", "Wdown")]
+                ("Wqkv", "Wo", "g_attn_norm", "g_ffn_norm", "Wr", "Wgateup", "Wdown",
+                 "Sqkv", "So", "Sgateup", "Sdown")]
 
 
 class MoeSets(C.Structure):

@@ -116,7 +116,8 @@ struct af_gemv_args {
   // slot s uses the matrix at W + w_sel[s] * w_stride elements (leading dimension ld), w_sel
   // being device memory.  w_sel == null: one matrix, one slot.
   const int32_t* w_sel;
-  long long w_stride;
+  long long w_stride;         // fp16: elements per matrix; q4: bytes of packed nibbles per matrix
+  long long w_stride_scales;  // q4: scale elements per matrix
   int n_slots;
   const float* y_scale;  // device scalar multiplying the product before the residual (null: 1)
 };

@@ -30,9 +30,16 @@ struct Q4Params {
   int out, ld, y_kind, out_pad, use_lds_x;
   int range_sel;  // threshold selection per channel range, no list for the whole vector
   int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
+  // output slots over device-selected matrices, as in the fp16 kernel: slot s reads the packed
+  // rows at packed + w_sel[s] * w_stride bytes and the scales at scales + w_sel[s] * s_stride
+  int cols_per_slot, tiles_per_slot;
+  const int* w_sel;
+  long long w_stride, s_stride;
+  const float* y_scale;
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
+  if (p.y_scale) v *= *p.y_scale;
   if (p.residual) v += (float)p.residual[col];
   if (p.y_kind == AF_F16)
     reinterpret_cast<half_t*>(p.y)[col] = (half_t)v;
@@ -81,8 +88,10 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
-  const int col = blockIdx.x * TW + lx * 8;
-  const int col_ld = col < p.out ? col : 0;
+  const int slot_o = blockIdx.x / p.tiles_per_slot;
+  const int tile_in = blockIdx.x - slot_o * p.tiles_per_slot;
+  const int col = tile_in * TW + lx * 8;  // column inside the slot
+  const int col_ld = col < p.cols_per_slot ? col : tile_in * TW;
   const int S = gridDim.y, s = blockIdx.y;
   const int slot = wave * LY + ly;
   const af_row_src& r = p.rows;
@@ -100,6 +109,12 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   for (int c = 0; c < 8; ++c) sc[c] = (half_t)0;
   const size_t row_bytes = (size_t)(p.ld / 2);
   const unsigned char* wcol = p.packed + col_ld / 2;
+  const half_t* sbase = p.scales;
+  if (p.w_sel) {
+    const int e_sel = p.w_sel[slot_o];
+    wcol += (size_t)e_sel * (size_t)p.w_stride;
+    sbase += (size_t)e_sel * (size_t)p.s_stride;
+  }
 
   auto consume = [&](unsigned e, unsigned w) {
     const int g = (int)(e >> 21);  // (index >> 5)
@@ -110,14 +125,14 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
         acc[c] = 0.f;
       }
       cur_g = g;
-      sc = *reinterpret_cast<const half8*>(p.scales + (size_t)g * p.ld + col_ld);
+      sc = *reinterpret_cast<const half8*>(sbase + (size_t)g * p.ld + col_ld);
     }
     const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu));
     q4_fma8(acc, w, xv, xv * 0.0625f);
   };
   // channel-local scales: the row's scale of this lane's column group multiplies x
   const size_t srow = (size_t)(p.ld / 32);
-  const half_t* scol = p.scales + col_ld / 32;
+  const half_t* scol = sbase + col_ld / 32;
   auto consume_cl = [&](unsigned e, unsigned w, half_t s_row) {
     const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e & 0xFFFFu)) * (float)s_row;
     q4_fma8(yacc, w, xv, xv * 0.0625f);
@@ -210,15 +225,15 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   }
   __syncthreads();
 
-  const int tile0 = blockIdx.x * TW;
+  const int tile0 = blockIdx.x * TW;                        // in the padded column space
+  const int out0 = slot_o * p.cols_per_slot + tile_in * TW;  // first output column of the tile
+  const int valid = min(TW, p.cols_per_slot - tile_in * TW);
   if (S == 1) {
-    for (int c = tid; c < TW; c += THREADS) {
-      if (tile0 + c < p.out) {
-        float v = 0.f;
+    for (int c = tid; c < valid; c += THREADS) {
+      float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) v += s_red[w][c];
-        q4_store_out(p, tile0 + c, v);
-      }
+      for (int w = 0; w < NW; ++w) v += s_red[w][c];
+      q4_store_out(p, out0 + c, v);
     }
     return;
   }
@@ -237,11 +252,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   }
   __syncthreads();
   if (!s_last) return;
-  for (int c = tid; c < TW; c += THREADS) {
-    if (tile0 + c < p.out) {
-      q4_store_out(p, tile0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
-    }
-  }
+  for (int c = tid; c < valid; c += THREADS)
+    q4_store_out(p, out0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
@@ -289,7 +301,12 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
     if (v == 4 || v == 16) nw = v;
   }
   const int tw = lx * 8;
-  const int tiles = (a.out + tw - 1) / tw;
+  const int n_slots = a.w_sel ? a.n_slots : 1;
+  if (n_slots < 1 || a.out % n_slots) return AF_EINVAL;
+  const int cols_per_slot = a.out / n_slots;
+  if (cols_per_slot % (a.q4_channel_local ? 32 : 8)) return AF_ESHAPE;
+  const int tiles_per_slot = (cols_per_slot + tw - 1) / tw;
+  const int tiles = n_slots * tiles_per_slot;
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
   int target = nw == 16 ? ctx->n_cu : ctx->n_cu * 4;
@@ -327,6 +344,12 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   p.use_lds_x = use_lds_x ? 1 : 0;
   p.range_sel = range_sel ? 1 : 0;
   p.list_off = (int)xs_bytes;
+  p.cols_per_slot = cols_per_slot;
+  p.tiles_per_slot = tiles_per_slot;
+  p.w_sel = a.w_sel;
+  p.w_stride = a.w_stride;      // bytes of packed nibbles per matrix
+  p.s_stride = a.w_stride_scales;  // scale elements per matrix
+  p.y_scale = a.y_scale;
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

@@ -566,12 +566,14 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
   const af_layer_cfg* cfg = &mcfg->base;
   int rc = check_layer_args(ctx, cfg, sel, kv_len, kv_cap, pos);
   if (rc) return rc;
-  if (cfg->weight_kind != AF_W_F16) return AF_EINVAL;
+  const bool q4 = cfg->weight_kind != AF_W_F16;
+  const bool cl = cfg->weight_kind == AF_W_Q4CL;
   if (mcfg->n_experts < 1 || mcfg->n_experts > AF_MOE_MAX_EXPERTS) return AF_EINVAL;
   if (mcfg->top < 1 || mcfg->top > AF_MOE_MAX_TOP || mcfg->top > mcfg->n_experts) return AF_EINVAL;
   if (sel->reuse_mask & 15u) return AF_EINVAL;
   if (!w->Wqkv || !w->Wo || !w->g_attn_norm || !w->g_ffn_norm || !w->Wr || !w->Wgateup || !w->Wdown)
     return AF_ENULL;
+  if (q4 && (!w->Sqkv || !w->So || !w->Sgateup || !w->Sdown)) return AF_ENULL;
   if (!route->experts || !route->weights || !route->logits) return AF_ENULL;
   const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim, top = mcfg->top;
   const int qdim = cfg->n_heads * hd, qkv_out = (cfg->n_heads + 2 * cfg->n_kv_heads) * hd;
@@ -594,6 +596,7 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
   auto gemv = [&](int point, int cfg_p, af_gemv_args& a, int producer, const half_t* src_v,
                   const half_t* gain, half_t* x) -> int {
     a.y_kind = AF_F16;
+    a.q4_channel_local = cl;
     af_row_src& r = a.rows;
     r.n = a.in;
     r.eps = cfg->rms_eps;
@@ -614,18 +617,27 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
       r.idx = nullptr;
       r.nidx_host = a.in;
     }
-    return af_launch_gemv_f16(ctx, a);
+    return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a);
+  };
+  // per-expert strides of a bank [E][in][cols]: fp16 elements, or packed bytes + scale elements
+  auto bank = [&](af_gemv_args& a, int in, int cols) {
+    if (!q4) {
+      a.w_stride = (long long)in * cols;
+    } else {
+      a.w_stride = (long long)in * (cols / 2);
+      a.w_stride_scales = cl ? (long long)in * (cols / 32) : (long long)(in / 32) * cols;
+    }
   };
 
   {
     af_gemv_args a{};
-    a.W = w->Wqkv; a.in = d; a.out = qkv_out; a.ld = qkv_out; a.y = qkv;
+    a.W = w->Wqkv; a.scales = (const half_t*)w->Sqkv; a.in = d; a.out = qkv_out; a.ld = qkv_out; a.y = qkv;
     if ((rc = gemv(0, 0, a, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0))) return rc;
   }
   if ((rc = launch_attention(ctx, cfg, qkv, k_cache, v_cache, kv_len, kv_cap, pos, attn))) return rc;
   {
     af_gemv_args a{};
-    a.W = w->Wo; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;
+    a.W = w->Wo; a.scales = (const half_t*)w->So; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;
     if ((rc = gemv(1, 1, a, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
   }
   {
@@ -653,15 +665,17 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
   }
   {
     af_gemv_args a{};
-    a.W = w->Wgateup; a.in = d; a.out = top * 2 * f; a.ld = 2 * f; a.y = gu;
-    a.w_sel = route->experts; a.w_stride = (long long)d * 2 * f; a.n_slots = top;
+    a.W = w->Wgateup; a.scales = (const half_t*)w->Sgateup; a.in = d; a.out = top * 2 * f; a.ld = 2 * f; a.y = gu;
+    a.w_sel = route->experts; a.n_slots = top;
+    bank(a, d, 2 * f);
     if ((rc = gemv(2, 2, a, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2))) return rc;
   }
   for (int s = 0; s < top; ++s) {
     af_gemv_args a{};
-    a.W = w->Wdown; a.in = f; a.out = d; a.ld = d; a.y = h_out;
+    a.W = w->Wdown; a.scales = (const half_t*)w->Sdown; a.in = f; a.out = d; a.ld = d; a.y = h_out;
     a.residual = s == 0 ? hmid : h_out;
-    a.w_sel = route->experts + s; a.w_stride = (long long)f * d; a.n_slots = 1;
+    a.w_sel = route->experts + s; a.n_slots = 1;
+    bank(a, f, d);
     a.y_scale = route->weights + s;
     if ((rc = gemv(3 + s, 3, a, AF_PRO_SILUMUL, gu + (size_t)s * 2 * f, nullptr, x3 + (size_t)s * f)))
       return rc;

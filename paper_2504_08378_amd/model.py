@@ -153,36 +153,51 @@ class DeviceMoeLayer:
     attention-side matrices, g_attn, g_ffn, the router Wr [E][d] and per-expert lists Wgate,
     Wup [ffn][d], Wdown [d][ffn] (fp16 NumPy arrays or torch tensors)."""
 
-    def __init__(self, ctx: B.Context, shape, host: dict, top: int = 2):
-        self.ctx, self.shape, self.top = ctx, shape, top
+    def __init__(self, ctx: B.Context, shape, host: dict, top: int = 2, weight_kind=B.AF_W_F16):
+        self.ctx, self.shape, self.top, self.kind = ctx, shape, top, weight_kind
         d, f, hd, E = shape.d_model, shape.d_ffn, shape.head_dim, shape.n_experts
         nq, nkv = shape.n_heads * hd, shape.n_kv_heads * hd
         dev = ctx.device
         up = lambda a: (a.to(dev).contiguous() if torch.is_tensor(a)
                         else torch.from_numpy(np.ascontiguousarray(a)).to(dev))
 
-        def pack_into(parts, Wt):
+        def alloc(lead, n_in, ld):
+            """Weight (and scale) tensors of matrices [n_in][ld], with leading dims `lead`."""
+            if weight_kind == B.AF_W_F16:
+                return torch.empty(lead + (n_in, ld), dtype=torch.float16, device=dev), None
+            Wt = torch.empty(lead + (n_in, ld // 2), dtype=torch.uint8, device=dev)
+            if weight_kind == B.AF_W_Q4CL:
+                return Wt, torch.empty(lead + (n_in, ld // 32), dtype=torch.float16, device=dev)
+            return Wt, torch.empty(lead + (n_in // 32, ld), dtype=torch.float16, device=dev)
+
+        def pack_into(parts, Wt, Sc):
             col = 0
             for p in parts:
                 Wd = up(p)
                 torch.cuda.current_stream().synchronize()
-                ctx.pack_inmajor_f16(Wd, Wt, col0=col)
+                if weight_kind == B.AF_W_F16:
+                    ctx.pack_inmajor_f16(Wd, Wt, col0=col)
+                elif weight_kind == B.AF_W_Q4CL:
+                    ctx.pack_q4_cl(Wd, Wt, Sc, col0=col)
+                else:
+                    ctx.pack_q4_g32(Wd, Wt, Sc, col0=col)
                 ctx.synchronize()
                 col += p.shape[0]
                 del Wd
 
-        self.Wqkv = torch.empty((d, nq + 2 * nkv), dtype=torch.float16, device=dev)
-        pack_into([host["Wq"], host["Wk"], host["Wv"]], self.Wqkv)
-        self.Wo = torch.empty((nq, d), dtype=torch.float16, device=dev)
-        pack_into([host["Wo"]], self.Wo)
-        self.Wgateup = torch.empty((E, d, 2 * f), dtype=torch.float16, device=dev)
-        self.Wdown = torch.empty((E, f, d), dtype=torch.float16, device=dev)
+        self.Wqkv, self.Sqkv = alloc((), d, nq + 2 * nkv)
+        pack_into([host["Wq"], host["Wk"], host["Wv"]], self.Wqkv, self.Sqkv)
+        self.Wo, self.So = alloc((), nq, d)
+        pack_into([host["Wo"]], self.Wo, self.So)
+        self.Wgateup, self.Sgateup = alloc((E,), d, 2 * f)
+        self.Wdown, self.Sdown = alloc((E,), f, d)
         for e in range(E):
-            pack_into([host["Wgate"][e], host["Wup"][e]], self.Wgateup[e])
-            pack_into([host["Wdown"][e]], self.Wdown[e])
+            pack_into([host["Wgate"][e], host["Wup"][e]], self.Wgateup[e],
+                      None if self.Sgateup is None else self.Sgateup[e])
+            pack_into([host["Wdown"][e]], self.Wdown[e], None if self.Sdown is None else self.Sdown[e])
         self.Wr = up(host["Wr"])
         self.g_attn, self.g_ffn = up(host["g_attn"]), up(host["g_ffn"])
-        self.cfg = B.MoeCfg(layer_cfg(shape), E, top)
+        self.cfg = B.MoeCfg(layer_cfg(shape, weight_kind), E, top)
         widths = (d, nq, d) + (f,) * top
         self.widths = widths
         self.idx = [torch.zeros(n, dtype=torch.int32, device=dev) for n in widths]
@@ -193,9 +208,10 @@ class DeviceMoeLayer:
         torch.cuda.current_stream().synchronize()
 
     def weights_struct(self) -> B.MoeWeights:
-        p = lambda t: t.data_ptr()
+        p = lambda t: t.data_ptr() if t is not None else None
         return B.MoeWeights(p(self.Wqkv), p(self.Wo), p(self.g_attn), p(self.g_ffn), p(self.Wr),
-                            p(self.Wgateup), p(self.Wdown))
+                            p(self.Wgateup), p(self.Wdown), p(self.Sqkv), p(self.So), p(self.Sgateup),
+                            p(self.Sdown))
 
     def sets_struct(self) -> B.MoeSets:
         s = B.MoeSets()

@@ -45,13 +45,32 @@ def _sets_close(got, ref, x_ref):
     return len(got) == len(ref) and np.all(np.abs(key[diff] - thr) <= 2)
 
 
-@pytest.mark.parametrize("sp", [50, 70])
-def test_moe_layer_topk(ctx, sp):
+def _quantised(w, kind):
+    """The oracle's view of the weights for a 4-bit kind: every matrix but the router quantised
+    by the oracle's own quantiser (the device packer's bits are checked in test_gpu_q4)."""
+    if kind == B.AF_W_F16:
+        return w, False
+    q = O.quantize_q4_cl if kind == B.AF_W_Q4CL else O.quantize_q4_g32
+    out = {}
+    for k, v in w.items():
+        if k == "Wr" or not k.startswith("W"):
+            out[k] = v
+        elif isinstance(v, list):
+            out[k] = [q(m) for m in v]
+        else:
+            out[k] = q(v)
+    return out, ("cl" if kind == B.AF_W_Q4CL else True)
+
+
+@pytest.mark.parametrize("sp,kind", [(50, B.AF_W_F16), (70, B.AF_W_F16), (50, B.AF_W_Q4G32), (50, B.AF_W_Q4CL)])
+def test_moe_layer_topk(ctx, sp, kind):
     shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 11)
     ks = tuple(O.keep_count(n, sp) for n in widths)
-    tr = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_TOPK, ks))
+    wq, q4 = _quantised(w, kind)
+    tr = O.decode_moe_layer(cfg, wq, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_TOPK, ks),
+                            weights_q4=q4)
     assert _margin_ok(tr)
-    lay = M.DeviceMoeLayer(ctx, shape, w)
+    lay = M.DeviceMoeLayer(ctx, shape, w, weight_kind=kind)
     Kd, Vd = to_dev(K), to_dev(V)
     hin = to_dev(h); hout = torch.zeros_like(hin)
     lay.run(hin, hout, Kd, Vd, KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
