@@ -61,7 +61,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   constexpr int SCRATCH = RP_SCRATCH_WORDS > NW * TW ? RP_SCRATCH_WORDS : NW * TW;
   typedef RowPrologue<GEMV_THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];  // the operator input, when built here
-  __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
+  __shared__ __align__(16) unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
   __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
   float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   constexpr int SCRATCH = RP_SCRATCH_WORDS > NW * TW ? RP_SCRATCH_WORDS : NW * TW;
   typedef RowPrologue<THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];
-  __shared__ unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
+  __shared__ __align__(16) unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
   __shared__ typename RP::Smem s_rp;
   __shared__ int s_last;
   float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);

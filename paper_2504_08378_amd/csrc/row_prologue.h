@@ -16,7 +16,6 @@ struct RowPrologue {
   static constexpr int WAVES = THREADS / AF_WAVE;
 
   struct Smem {
-    unsigned merged[256];
     unsigned wave_tot[WAVES];
     float red[WAVES];
     unsigned digit, above;
@@ -33,11 +32,21 @@ struct RowPrologue {
     for (int i = threadIdx.x; i < RP_SCRATCH_WORDS; i += THREADS) hist[i] = 0;
   }
 
+  // first-digit counts of one 8-element vector into this lane's replica
+  static __device__ __forceinline__ void count_digit1(unsigned* hist, const half8& h) {
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const u16x8 b = __builtin_bit_cast(u16x8, h);
+    const int rep = threadIdx.x & (RP_HIST_COPIES - 1);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
+  }
+
   // Fill xs[0..n) with the fp16 bits of the operator input (n % 8 == 0).  Global reads are
   // 16-byte vectors issued four at a time, so a thread waits for memory once per batch and
   // not once per element.
-  // `hist`, when given, is cleared on the way (select_split is then told so), which saves the
-  // selection a barrier.
+  // `hist`, when given (top-k selection follows), receives the histogram of the first radix
+  // digit on the way: the values are counted while they are still in registers, which saves
+  // the selection a pass over LDS and two barriers (select_split is told so).
   static __device__ __forceinline__ void produce(const af_row_src& r, unsigned short* xs, Smem& sm,
                                                  bool store_x, int store_phase, int store_stride,
                                                  unsigned* hist = nullptr) {
@@ -49,6 +58,10 @@ struct RowPrologue {
     half8 zero;
 #pragma unroll
     for (int c = 0; c < 8; ++c) zero[c] = (half_t)0;
+    if (hist != nullptr) {
+      zero_hist(hist);
+      if (r.pro != AF_PRO_RMSNORM) __syncthreads();  // the norm has a barrier of its own before it counts
+    }
     if (r.pro == AF_PRO_NONE) {
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
         half8 t[B];
@@ -56,7 +69,10 @@ struct RowPrologue {
         for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
 #pragma unroll
         for (int u = 0; u < B; ++u)
-          if (v0 + u * THREADS < nvec) xv[v0 + u * THREADS] = t[u];
+          if (v0 + u * THREADS < nvec) {
+            xv[v0 + u * THREADS] = t[u];
+            if (hist != nullptr) count_digit1(hist, t[u]);
+          }
       }
     } else if (r.pro == AF_PRO_RMSNORM) {
       const half8* gain = reinterpret_cast<const half8*>(r.gain);
@@ -100,6 +116,7 @@ struct RowPrologue {
 #pragma unroll
             for (int c = 0; c < 8; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
             xv[v0 + u * THREADS] = h;
+            if (hist != nullptr) count_digit1(hist, h);
           }
         }
       }
@@ -123,11 +140,11 @@ struct RowPrologue {
               h[c] = (half_t)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * (float)u8[u][c]);
             }
             xv[v0 + u * THREADS] = h;
+            if (hist != nullptr) count_digit1(hist, h);
           }
         }
       }
     }
-    if (hist != nullptr) zero_hist(hist);
     __syncthreads();
     if (store_x && r.x_out != nullptr) {
       half8* dst = reinterpret_cast<half8*>(r.x_out);
@@ -138,24 +155,26 @@ struct RowPrologue {
   // digit d with count(digit > d) < want <= count(digit >= d); result in sm.digit / sm.above
   static __device__ __forceinline__ void find_digit(const unsigned* hist, Smem& sm, int nbins,
                                                     unsigned want) {
+    // The first wave sums the replicas itself, four neighbouring bins per lane and 16 bytes
+    // per LDS read, and scans them; the others only wait for the answer (one barrier).
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x;
-    for (int b = tid; b < 256; b += THREADS) {
-      unsigned s = 0;
-      if (b < nbins) {
-#pragma unroll
-        for (int c = 0; c < RP_HIST_COPIES; ++c) s += hist[c * nbins + b];
-      }
-      sm.merged[b] = s;
-    }
-    __syncthreads();
     if (tid < AF_WAVE) {
-      const unsigned b0 = sm.merged[4 * tid], b1 = sm.merged[4 * tid + 1],
-                     b2 = sm.merged[4 * tid + 2], b3 = sm.merged[4 * tid + 3];
-      const unsigned mine = b0 + b1 + b2 + b3;
+      unsigned cnt[4] = {0u, 0u, 0u, 0u};
+      if (4 * tid < nbins) {
+#pragma unroll
+        for (int c = 0; c < RP_HIST_COPIES; ++c) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(hist + c * nbins + 4 * tid);
+          cnt[0] += v[0];
+          cnt[1] += v[1];
+          cnt[2] += v[2];
+          cnt[3] += v[3];
+        }
+      }
+      const unsigned mine = cnt[0] + cnt[1] + cnt[2] + cnt[3];
       const unsigned pre = af_wave_incl_scan(mine);                       // bins of lanes <= mine
       const unsigned all = (unsigned)__builtin_amdgcn_readlane((int)pre, 63);
       unsigned above = all - pre;                                         // bins of higher lanes
-      const unsigned cnt[4] = {b0, b1, b2, b3};
 #pragma unroll
       for (int q = 3; q >= 0; --q) {
         if (above < want && want <= above + cnt[q]) {
@@ -352,7 +371,7 @@ struct RowPrologue {
   static __device__ __forceinline__ int select_split(const af_row_src& r, const unsigned short* xs,
                                                      unsigned* hist, Smem& sm, unsigned* list,
                                                      int S, int s, bool store_idx, bool store_count,
-                                                     int* nidx_total, bool hist_zeroed = false) {
+                                                     int* nidx_total, bool digit1_counted = false) {
     typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
     const int tid = threadIdx.x, lane = tid & 63;
     const int nvec = r.n >> 3;
@@ -374,17 +393,17 @@ struct RowPrologue {
       T = threshold_key(r.t);
     }
     if (topk && r.k > 0) {
-      if (!hist_zeroed) {
+      if (!digit1_counted) {
         zero_hist(hist);
         __syncthreads();
-      }
-      for (int v = v0; v < v1; ++v) {
-        const u16x8 b = xv[v];
+        for (int v = v0; v < v1; ++v) {
+          const u16x8 b = xv[v];
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
-          atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
+          for (int c = 0; c < 8; ++c)
+            atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
+        }
+        __syncthreads();
       }
-      __syncthreads();
       find_digit(hist + H1, sm, 256, (unsigned)r.k);
       const unsigned d1 = sm.digit, above1 = sm.above;
       for (int v = v0; v < v1; ++v) {

@@ -14,7 +14,7 @@
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(af_row_src r, int n_valid) {
   typedef RowPrologue<SEL_THREADS> RP;
   extern __shared__ __align__(16) unsigned short xs[];
-  __shared__ unsigned s_scratch[RP_SCRATCH_WORDS];
+  __shared__ __align__(16) unsigned s_scratch[RP_SCRATCH_WORDS];
   __shared__ typename RP::Smem s_rp;
   const int tid = threadIdx.x;
   const unsigned short* src = reinterpret_cast<const unsigned short*>(r.src);
