@@ -146,18 +146,38 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
     for (; i + U <= iend; i += U) {
       unsigned w[U], e[U];
       half_t sr[U];
+      half8 sg[U];  // group-32 layout: the scales of a row that opens a new group, fetched with the batch
+      int gprev = cur_g;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         e[u] = s_list[i + u];
         w[u] = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes);
-        if (CL) sr[u] = scol[(size_t)(e[u] >> 16) * srow];
+        if (CL) {
+          sr[u] = scol[(size_t)(e[u] >> 16) * srow];
+        } else {
+          const int g = (int)(e[u] >> 21);
+          if (g != gprev) sg[u] = *reinterpret_cast<const half8*>(sbase + (size_t)g * p.ld + col_ld);
+          gprev = g;
+        }
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        if (CL)
+        if (CL) {
           consume_cl(e[u], w[u], sr[u]);
-        else
-          consume(e[u], w[u]);
+        } else {
+          const int g = (int)(e[u] >> 21);
+          if (g != cur_g) {  // fold the finished group, switch to the scales that came with the batch
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              yacc[c] += (float)sc[c] * acc[c];
+              acc[c] = 0.f;
+            }
+            cur_g = g;
+            sc = sg[u];
+          }
+          const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e[u] & 0xFFFFu));
+          q4_fma8(acc, w[u], xv, xv * 0.0625f);
+        }
       }
     }
     // Ragged end: one more batch of the same depth with the missing rows masked off, so its
