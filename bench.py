@@ -26,9 +26,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel (fused gate|up GEMV, 7B shape, 50 %) from the
 # two rocprofv3 --pmc runs summarised in profiles/gateup_7b_f16_sp50_pmc_traffic.md:
-# FETCH_SIZE 44441.5 KiB x 2.000 + WRITE_SIZE 497.2 KiB x 1.000, the factors being what the same
+# FETCH_SIZE 44452.9 KiB x 2.000 + WRITE_SIZE 497.2 KiB x 1.000, the factors being what the same
 # counters read for a plain 256 MiB device copy (131083.5 and 262144.0 KiB).
-TRAFFIC_BYTES_PER_LAUNCH = {("7b", "f16", 50): int((44441.5 * 2.0 + 497.2) * 1024)}
+TRAFFIC_BYTES_PER_LAUNCH = {("7b", "f16", 50): int((44452.9 * 2.0 + 497.2) * 1024)}
 
 
 def keep_count(n: int, sp: int) -> int:
