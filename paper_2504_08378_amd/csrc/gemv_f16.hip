@@ -13,6 +13,10 @@
 // Front end (row_prologue.h): the kernel can build its input vector itself (RMSNorm of the
 // residual stream, SiLU(gate)*up) and run the top-k / threshold selection on it, each
 // workgroup for itself, which removes the separate selection kernels from a decoder layer.
+// With thresholds and no index list asked for, a workgroup decides only the channels of its
+// own range (split by channel position instead of list position).
+// Matrices picked on the device (mixture of experts): the output columns form slots of whole
+// tiles and slot s reads W + w_sel[s] * w_stride, w_sel being device memory.
 // Reduction: lane groups by wave shuffles, waves through LDS, splits through an fp32
 // partials buffer; the workgroup that arrives last at a tile's ticket adds the S partials in
 // split order, so the result does not depend on scheduling.
@@ -238,9 +242,9 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
   // workgroup) win up to ~16K columns, 512-column tiles (1 KB) beyond.  With 256-column tiles
   // on a row stride that is a multiple of 1 KB every workgroup stays on one value of address
   // bit 9 for all its rows, and the half of the workgroups on one of the two values finished
-  // ~2 us after the other half.  A kernel that selects for
-  // itself (or builds its input vector) repeats that work in every workgroup, so it runs few, large workgroups
-  // (one per CU); a plain GEMV prefers several small ones per CU.
+  // ~2 us after the other half.  A kernel that selects for itself (or builds its input
+  // vector) repeats that work in every workgroup, so it runs few, large workgroups (one per
+  // CU); a plain GEMV prefers several small ones per CU.
   int lx = out <= 16384 ? 16 : 64;
   int nw = selects ? 16 : 4;
   if (const char* e = getenv("AF_GEMV_LX")) {
