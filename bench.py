@@ -116,6 +116,55 @@ def union_bench(args, S, B, torch, np) -> int:
     return 0
 
 
+def config0_bench(args, S, B, torch, np) -> int:
+    """--config0: one 2048x2048 fp16 layer, top-k 50 % (k = 1024), selection fused into the GEMV.
+    4 MB of active weights fit every cache, so the launch is timed cold (rotating through 160
+    distinct matrices, 1.3 GB) and warm (one matrix) separately; only cold counts against HBM."""
+    n = out = 2048
+    k = keep_count(n, 50)
+    ctx = B.Context(0)
+    x = torch.from_numpy(S.activation(0, S.channel_scales(0, n, "config0"), "config0", 0)).cuda()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(0)
+    mats = [(torch.randn((n, out), generator=gen, device="cuda") * 0.02).to(torch.float16) for _ in range(160)]
+    y = torch.empty(out, dtype=torch.float16, device="cuda")
+    idx = torch.empty(n, dtype=torch.int32, device="cuda"); cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    call = lambda W: ctx.select_gemv_f16(W, x, sel_mode=B.AF_SEL_TOPK, k=k, idx_out=idx, count_out=cnt, y=y)
+
+    def timed(seq, reps):
+        for W in seq[:8]:
+            call(W)
+        ctx.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(ctx.stream)
+        for _ in range(reps):
+            for W in seq:
+                call(W)
+        e1.record(ctx.stream)
+        ctx.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * len(seq))
+
+    cold_us = timed(mats, max(1, args.steps // 40))
+    warm_us = timed(mats[:1] * 40, max(1, args.steps // 10))
+    alg = gemv_bytes(k, out) + n * 2
+    out_j = {
+        "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+        "value": round(1e6 / cold_us, 1), "unit": "launches/s", "n_gpus": 1, "steps": args.steps, "warmup": 8,
+        "ms_per_step": round(cold_us * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "config 0: one 2048x2048 fp16 layer, top-k 50 % fused into the GEMV, batch 1"},
+        "cold_us_per_launch": round(cold_us, 3), "warm_us_per_launch": round(warm_us, 3),
+        "roofline": {"bound": "hbm", "kernel": "gemv_f16_kernel<16, 8, 16> (top-k + gathered GEMV, cold matrices)",
+                     "achieved": round(alg / (cold_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(alg / (cold_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": alg, "us_per_launch": round(cold_us, 3)},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out_j))
+    ctx.close()
+    return 0
+
+
 def moe_bench(args, S, B, M, torch, np) -> int:
     """--shape mixtral: decoder blocks with a mixture-of-experts feed-forward half (8 experts,
     top-2).  Like the paper's technique evaluation it runs a slice of the model (8 layers by
@@ -277,6 +326,8 @@ def main() -> int:
                     help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
     ap.add_argument("--union", type=int, default=0, metavar="B",
                     help="small-batch union GEMV over the four operators of one layer of --shape (e.g. 70b) with B tokens")
+    ap.add_argument("--config0", action="store_true",
+                    help="the single 2048x2048 layer of BASELINE config 0, cold and warm")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (float4 per lane), the known-size "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -299,6 +350,8 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
 
+    if args.config0:
+        return config0_bench(args, S, B, torch, np)
     if args.union:
         return union_bench(args, S, B, torch, np)
     if S.MODEL_SHAPES[args.shape].n_experts:
