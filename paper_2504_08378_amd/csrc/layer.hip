@@ -503,13 +503,31 @@ __global__ __launch_bounds__(MOE_THREADS) void moe_router_kernel(RouterParams p)
   __shared__ typename RP::Smem s_rp;
   __shared__ float s_part[MOE_THREADS / AF_WAVE][AF_MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  RP::produce(p.rows, xs, s_rp, false, 0, 1);
   const int nvec = p.rows.n >> 3;
+  half8 zero8;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) zero8[c] = (half_t)0;
+  // the router rows of this thread's first vector do not depend on x: fetch them before x is
+  // built, so the two global round trips overlap
+  half8 w0[AF_MOE_MAX_EXPERTS];
+#pragma unroll
+  for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e)
+    w0[e] = (e < p.n_experts && tid < nvec)
+                ? *reinterpret_cast<const half8*>(p.Wr + (size_t)e * p.rows.n + (size_t)tid * 8)
+                : zero8;
+  RP::produce(p.rows, xs, s_rp, false, 0, 1);
   const half8* xv = reinterpret_cast<const half8*>(xs);
   float acc[AF_MOE_MAX_EXPERTS];
 #pragma unroll
   for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e) acc[e] = 0.f;
-  for (int v = tid; v < nvec; v += MOE_THREADS) {
+  if (tid < nvec) {
+    const half8 x8 = xv[tid];
+#pragma unroll
+    for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[e] += (float)w0[e][c] * (float)x8[c];
+  }
+  for (int v = tid + MOE_THREADS; v < nvec; v += MOE_THREADS) {  // inputs wider than 8192
     const half8 x8 = xv[v];
 #pragma unroll
     for (int e = 0; e < AF_MOE_MAX_EXPERTS; ++e) {
@@ -526,14 +544,20 @@ __global__ __launch_bounds__(MOE_THREADS) void moe_router_kernel(RouterParams p)
     if (lane == 0) s_part[wave][e] = t;
   }
   __syncthreads();
-  if (tid != 0) return;
-  float logit[AF_MOE_MAX_EXPERTS];
-  for (int e = 0; e < p.n_experts; ++e) {
+  if (tid >= AF_WAVE) return;
+  // lane e adds the wave sums of expert e in wave order; thread 0 then picks
+  __shared__ float s_logit[AF_MOE_MAX_EXPERTS];
+  if (lane < p.n_experts) {
     float t = 0.f;
-    for (int w = 0; w < MOE_THREADS / AF_WAVE; ++w) t += s_part[w][e];
-    logit[e] = t;
-    p.logits[e] = t;
+#pragma unroll
+    for (int w = 0; w < MOE_THREADS / AF_WAVE; ++w) t += s_part[w][lane];
+    s_logit[lane] = t;
+    p.logits[lane] = t;
   }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  if (tid != 0) return;
+  const float* logit = s_logit;  // indexed at run time: stays in LDS
   int chosen[AF_MOE_MAX_TOP];
   float z[AF_MOE_MAX_TOP];
   unsigned taken = 0;
