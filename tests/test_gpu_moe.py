@@ -184,3 +184,21 @@ def test_expert_indexed_gemv(ctx, cols, n, E, slots):
     idx_t = O.select_threshold(x, t)
     ref = res.astype(np.float64) + 0.375 * np.concatenate([O.sparse_gemv(Ws[e], x, idx_t) for e in sel])
     assert O.rel_err(to_host(y), ref) <= TOL
+
+
+@pytest.mark.parametrize("top", [1, 3])
+def test_moe_other_top_counts(ctx, top):
+    """One expert per token, and three of four: slot handling beyond the usual top-2."""
+    shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 13)
+    ks = tuple(O.keep_count(n, 50) for n in widths)
+    tr = O.decode_moe_layer(cfg, w, h, K.copy(), V.copy(), KV_LEN, KV_LEN, O.SelectCfg(O.SEL_TOPK, ks), top=top)
+    assert _margin_ok(tr)
+    lay = M.DeviceMoeLayer(ctx, shape, w, top=top)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    lay.run(hin, hout, to_dev(K), to_dev(V), KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
+    ctx.synchronize()
+    assert to_host(lay.experts).tolist() == tr.experts.tolist()
+    assert np.allclose(to_host(lay.weights), tr.weights, rtol=1e-4)
+    same = all(np.array_equal(to_host(lay.idx[p])[: ks[p]], tr.idx[p]) for p in range(3))
+    same &= all(np.array_equal(to_host(lay.idx[3 + s])[: ks[3]], tr.idx_down[s]) for s in range(top))
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
