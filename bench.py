@@ -189,12 +189,45 @@ def moe_bench(args, S, B, M, torch, np) -> int:
     bufs = [torch.zeros_like(hin), torch.zeros_like(hin)]
     torch.cuda.synchronize()
     t_build = time.time() - t_build
-    sel = M.select_cfg(B.AF_SEL_TOPK, ks)
+    sel_topk = M.select_cfg(B.AF_SEL_TOPK, ks)
+    sels = [sel_topk] * L
+    keep_frac = None
+    if args.select == "threshold":
+        # calibration as in the dense-FFN stack: pool the operator inputs of a top-k run over
+        # --calib-tokens tokens; the down point pools the inputs of all chosen experts
+        hists = [[ctx.calib_hist() for _ in range(4)] for _ in range(L)]
+        torch.cuda.synchronize()
+        scales = S.channel_scales(0, d, shape.name)
+        taps = ((0, d), (2, widths[1]), (4, d), (6, top * f))
+        for tok in range(1, args.calib_tokens + 1):
+            cur = torch.from_numpy(S.activation(0, scales, "hidden", tok)).cuda()
+            torch.cuda.synchronize()
+            for l in range(L):
+                layers[l].run(cur, bufs[l & 1], kv[l][0], kv[l][1], kv_len, kv_cap, kv_len, sel_topk)
+                ctx.synchronize()
+                for p_, (tap, n_) in enumerate(taps):
+                    ctx.calib_accumulate(ctx.layer_tap(tap, n_), hists[l][p_])
+                cur = bufs[l & 1]
+            ctx.synchronize()
+        t_dev = [[ctx.calib_thresholds(hists[l][p_], [sp]) for p_ in range(4)] for l in range(L)]
+        ctx.synchronize()
+        thr = [[float(t_dev[l][p_].item()) for p_ in range(4)] for l in range(L)]
+        cur = hin
+        kept = []
+        for l in range(L):   # kept fractions on the bench token (sets written)
+            layers[l].run(cur, bufs[l & 1], kv[l][0], kv[l][1], kv_len, kv_cap, kv_len,
+                          M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l]))
+            ctx.synchronize()
+            c = [int(layers[l].count[p_].item()) for p_ in range(3 + top)]
+            kept.append([c[0], c[1], c[2], sum(c[3:]) / top])
+            cur = bufs[l & 1]
+        keep_frac = [round(sum(k_[p_] for k_ in kept) / (L * widths[p_]), 4) for p_ in range(4)]
+        sels = [M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l], flags=B.AF_SEL_SKIP_SETS) for l in range(L)]
 
     def run():
         cur = hin
         for l in range(L):
-            layers[l].run(cur, bufs[l & 1], kv[l][0], kv[l][1], kv_len, kv_cap, kv_len, sel)
+            layers[l].run(cur, bufs[l & 1], kv[l][0], kv[l][1], kv_len, kv_cap, kv_len, sels[l])
             cur = bufs[l & 1]
 
     run()
@@ -217,12 +250,14 @@ def moe_bench(args, S, B, M, torch, np) -> int:
     outs = (shape.qkv_out, d, top * 2 * f, d)
     mult = (1, 1, 1, top)                                   # the down projection runs once per slot
     bpw = 2.0 if kind == B.AF_W_F16 else 0.5
-    per_layer = sum(mult[p] * ks[p] * outs[p] for p in range(4)) * bpw
+    rows = ks if keep_frac is None else [keep_frac[p] * widths[p] for p in range(4)]   # mean active channels
+    per_layer = sum(mult[p] * rows[p] * outs[p] for p in range(4)) * bpw
     if kind == B.AF_W_Q4G32:
         per_layer += sum(mult[p] * (widths[p] // 32) * outs[p] for p in range(4)) * 2
     elif kind == B.AF_W_Q4CL:
-        per_layer += sum(mult[p] * ks[p] * (outs[p] // 32) for p in range(4)) * 2
+        per_layer += sum(mult[p] * rows[p] * (outs[p] // 32) for p in range(4)) * 2
     active_bytes = per_layer * L
+    sel_note = "" if keep_frac is None else f", threshold selection calibrated on {args.calib_tokens} tokens (no index lists)"
 
     roofline = None
     if kind != B.AF_W_F16:
@@ -233,8 +268,9 @@ def moe_bench(args, S, B, M, torch, np) -> int:
             "vs_baseline": None, "dtype": "int4", "data": "synthetic",
             "config": {"workload": f"{args.shape}-shape mixture-of-experts blocks ({shape.n_experts} experts, top-{top}), "
                                    f"{L} layers, batch-1 decode, {args.weights} weights, {sp}% sparsity at "
-                                   f"qkv/o/gate-up/down, {kv_len}-token KV cache", "layers": L, "d_model": d,
-                       "d_ffn": f, "k": list(ks), "graph": True, "experts_chosen_layer0": experts[0]},
+                                   f"qkv/o/gate-up/down, {kv_len}-token KV cache{sel_note}", "layers": L, "d_model": d,
+                       "d_ffn": f, "k": list(ks), "graph": True, "experts_chosen_layer0": experts[0],
+                       "kept_fraction_by_point": keep_frac},
             "active_weight_bytes_per_token": int(active_bytes),
             "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
             "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),
@@ -283,8 +319,8 @@ def moe_bench(args, S, B, M, torch, np) -> int:
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.shape}-shape mixture-of-experts blocks ({shape.n_experts} experts, top-{top}), "
                                f"{L} layers, batch-1 decode, f16 weights, {sp}% sparsity at qkv/o/gate-up/down, "
-                               f"{kv_len}-token KV cache", "layers": L, "d_model": d, "d_ffn": f, "k": list(ks),
-                   "graph": True, "experts_chosen_layer0": experts[0]},
+                               f"{kv_len}-token KV cache{sel_note}", "layers": L, "d_model": d, "d_ffn": f, "k": list(ks),
+                   "graph": True, "experts_chosen_layer0": experts[0], "kept_fraction_by_point": keep_frac},
         "active_weight_bytes_per_token": int(active_bytes),
         "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
         "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),

@@ -35,6 +35,8 @@ MODEL_SHAPES = {
     # a few-tile toy used by fast tests (ragged: ffn is not a power of two)
     "tiny": ModelShape("tiny", 4, 256, 4, 4, 64, 688),
     "tiny_gqa": ModelShape("tiny_gqa", 2, 512, 8, 2, 64, 1376),
+    # the head width of the real models (128) at toy size, grouped-query
+    "tiny_hd128": ModelShape("tiny_hd128", 2, 512, 4, 2, 128, 1376),
     "7b": ModelShape("7b", 32, 4096, 32, 32, 128, 11008),
     "13b": ModelShape("13b", 40, 5120, 40, 40, 128, 13824),
     "70b": ModelShape("70b", 1, 8192, 64, 8, 128, 28672),

@@ -467,3 +467,47 @@ def test_stack_per_layer_thresholds_skip_sets_and_reuse(ctx):
     # a wrong number of configurations is refused
     with pytest.raises(B.AfError):
         st.run(to_dev(h), KV_LEN, KV_LEN, sels[:3])
+
+
+def test_layer_head_dim_128_small(ctx):
+    """The real models' head width (128) on a toy layer, grouped-query, stage by stage."""
+    shape = S.MODEL_SHAPES["tiny_hd128"]
+    layers, kv, h = _host_stack(shape, 1, seed=10)
+    ks = _ks(shape, 50)
+    tr = O.decode_layer(_ocfg(shape), layers[0], h, kv[0][0].copy(), kv[0][1].copy(), KV_LEN, KV_LEN,
+                        O.SelectCfg(O.SEL_TOPK, ks))
+    st = _dev_stack(ctx, shape, layers, kv)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    st.sets[0].load(tr.idx)
+    st.layer(0, hin, hout, KV_LEN, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+    ctx.synchronize()
+    t = _taps(ctx, shape)
+    assert O.rel_err(t["qkv"], tr.qkv) <= TOL
+    assert O.rel_err(t["attn"], tr.attn, 1.0) <= TOL
+    assert O.rel_err(t["h_mid"], tr.h_mid, 1.0) <= TOL
+    assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= TOL
+    assert np.array_equal(to_host(st.K[0])[:, KV_LEN], tr.k_new) and np.array_equal(to_host(st.V[0])[:, KV_LEN], tr.v_new)
+    # several key splits: a longer cache
+    kv_len, kv_cap = 300, 304
+    layers2, kv2, h2 = _host_stack(shape, 1, seed=11, kv_len=kv_len, kv_cap=kv_cap)
+    tr2 = O.decode_layer(_ocfg(shape), layers2[0], h2, kv2[0][0].copy(), kv2[0][1].copy(), kv_len, kv_len,
+                         O.SelectCfg(O.SEL_TOPK, ks))
+    st2 = _dev_stack(ctx, shape, layers2, kv2, kv_cap=kv_cap)
+    st2.sets[0].load(tr2.idx)
+    st2.layer(0, to_dev(h2), hout, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks, reuse_mask=0b1111))
+    ctx.synchronize()
+    assert O.rel_err(_taps(ctx, shape)["attn"], tr2.attn, 1.0) <= TOL
+    assert O.rel_err(to_host(hout), tr2.hidden, 1.0) <= TOL
+
+
+def test_stack_selection_config_count_is_checked(ctx):
+    shape = S.MODEL_SHAPES["tiny"]
+    layers, kv, h = _host_stack(shape, 3)
+    st = _dev_stack(ctx, shape, layers, kv)
+    sel = M.select_cfg(B.AF_SEL_TOPK, _ks(shape, 50))
+    for bad in ([sel, sel], [sel] * 4):
+        with pytest.raises(B.AfError) as e:
+            st.run(to_dev(h), KV_LEN, KV_LEN, bad)
+        assert e.value.status == -1
+    st.run(to_dev(h), KV_LEN, KV_LEN, [sel] * 3)
+    ctx.synchronize()
