@@ -76,13 +76,13 @@ struct af_row_src {
 #define AF_GEMV_LDS_BUDGET (120u * 1024u)  // leaves room for the kernels' static LDS in 160 KB
 static inline bool af_plan_gemv_lds(const af_row_src& r, int max_rows, bool use_lds_x,
                                     bool range_sel, int chunk, int* S, size_t* xs_bytes,
-                                    int* list_cap) {
+                                    int* list_cap, bool full_x = false) {
   for (int s = *S < 1 ? 1 : *S; s <= 4096; ++s) {
     size_t xb;
     int cap;
     if (range_sel) {
       cap = 8 * ((r.n / 8 + s - 1) / s);  // a channel range, whole 8-element vectors
-      xb = (size_t)cap * 2;
+      xb = full_x ? (size_t)r.n * 2 : (size_t)cap * 2;  // an in-kernel router wants all of x
     } else if (r.sel != AF_ROWS_GIVEN) {
       cap = (max_rows + s - 1) / s;
       xb = (size_t)r.n * 2;
@@ -120,6 +120,14 @@ struct af_gemv_args {
   long long w_stride_scales;  // q4: scale elements per matrix
   int n_slots;
   const float* y_scale;  // device scalar multiplying the product before the residual (null: 1)
+  // Router run inside this launch (see the kernels): valid for a norm producer, at most 8
+  // experts and in <= 8192; the slots then follow the experts found in the kernel (w_sel is
+  // not read) and the results are published to the three device arrays.
+  const half_t* router_Wr;
+  int router_E, router_top;
+  int32_t* router_experts;
+  float* router_weights;
+  float* router_logits;
 };
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);

@@ -44,6 +44,14 @@ struct GemvParams {
   const int* w_sel;
   long long w_stride;
   const float* y_scale;
+  // Router of a mixture-of-experts block run in this launch's front end (gate|up): every
+  // workgroup works out the experts itself from x and uses them for its slot; workgroup
+  // (0, 0) publishes them for the launches that follow.  Null router_Wr: no router.
+  const half_t* router_Wr;  // [router_E][in]
+  int router_E, router_top;
+  int32_t* router_experts;
+  float* router_weights;
+  float* router_logits;
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
@@ -55,7 +63,9 @@ __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v)
     reinterpret_cast<float*>(p.y)[col] = v;
 }
 
-template <int LX, int U, int NW>
+// ROUTED: the instantiation that runs a mixture-of-experts router in its front end (kept apart
+// so that the plain launches do not carry its registers).
+template <int LX, int U, int NW, bool ROUTED>
 __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   constexpr int GEMV_THREADS = NW * AF_WAVE;
   constexpr int GEMV_WAVES = NW;
@@ -97,15 +107,40 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
     }
   }
 
-  if (p.use_lds_x && !p.range_sel)
+  constexpr int RE = 8;  // experts the in-kernel router handles
+  constexpr bool routed = ROUTED;
+  half8 wr[routed ? RE : 1];
+  if constexpr (routed) {  // this thread's router weights do not depend on x: fetch them before x is built
+#pragma unroll
+    for (int e = 0; e < RE; ++e) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) wr[e][c] = (half_t)0;
+      if (e < p.router_E && tid < (r.n >> 3))
+        wr[e] = *reinterpret_cast<const half8*>(p.router_Wr + (size_t)e * r.n + (size_t)tid * 8);
+    }
+  }
+  if (p.use_lds_x && (!p.range_sel || routed))
     RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
                 r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
+  if constexpr (routed) {
+    RP::template router_in_lds<RE>(xs, r.n, s_rp, wr, p.router_E, p.router_top);
+    if (blockIdx.x == 0 && s == 0) {
+      if (tid < p.router_top) {
+        p.router_experts[tid] = s_rp.experts[tid];
+        p.router_weights[tid] = s_rp.weights[tid];
+      }
+      if (tid < p.router_E) p.router_logits[tid] = s_rp.logit[tid];
+    }
+  }
 
   float acc[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   const half_t* wcol = p.W + col_ld;
-  if (p.w_sel) wcol += (size_t)p.w_sel[slot] * (size_t)p.w_stride;
+  if (routed)
+    wcol += (size_t)s_rp.experts[slot] * (size_t)p.w_stride;
+  else if (p.w_sel)
+    wcol += (size_t)p.w_sel[slot] * (size_t)p.w_stride;
 
   // One pass over `cnt` staged rows of s_list.
   auto stream = [&](int cnt) {
@@ -152,7 +187,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   };
 
   if (p.range_sel) {
-    stream(RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
+    stream(routed ? RP::threshold_range_of_full(r, xs, s_rp, s_list, S, s)
+                  : RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
   } else if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
@@ -278,25 +314,27 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
   *s_out = S;
 }
 
-template <int LX, int NW>
+template <int LX, int NW, bool ROUTED>
 static void launch_one(dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW, ROUTED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW, ROUTED>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
 
 template <int LX>
 static void launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
-  if (nw == 16)
-    launch_one<LX, 16>(grid, lds, st, p);
+  if (p.router_Wr != nullptr)  // the launcher has made sure of nw == 16
+    launch_one<LX, 16, true>(grid, lds, st, p);
+  else if (nw == 16)
+    launch_one<LX, 16, false>(grid, lds, st, p);
   else if (nw == 8)
-    launch_one<LX, 8>(grid, lds, st, p);
+    launch_one<LX, 8, false>(grid, lds, st, p);
   else
-    launch_one<LX, 4>(grid, lds, st, p);
+    launch_one<LX, 4, false>(grid, lds, st, p);
 }
 
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
@@ -324,7 +362,10 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   int list_cap;
   // the split partial sums have to fit the workspace, the staged rows of a split the LDS
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, GEMV_LIST, &S, &xs_bytes, &list_cap))
+  if (a.router_Wr && (r.pro != AF_PRO_RMSNORM || a.router_E > 8 || r.n > 8192 || nw != 16 || !use_lds_x))
+    return AF_EINVAL;  // the in-kernel router's preconditions (the caller falls back to the router kernel)
+  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, GEMV_LIST, &S, &xs_bytes, &list_cap,
+                        a.router_Wr != nullptr))
     return AF_EWORKSPACE;
   if (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) return AF_EWORKSPACE;
   GemvParams p;
@@ -346,6 +387,12 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.w_sel = a.w_sel;
   p.w_stride = a.w_stride;
   p.y_scale = a.y_scale;
+  p.router_Wr = a.router_Wr;
+  p.router_E = a.router_E;
+  p.router_top = a.router_top;
+  p.router_experts = a.router_experts;
+  p.router_weights = a.router_weights;
+  p.router_logits = a.router_logits;
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

@@ -13,6 +13,7 @@
 //   5 gemv  Wdown    on silu(gate)*up, selecting, + h_mid -> x_down, idx3, hidden_out
 // (the same holds for 4-bit weights: gemv_q4.hip shares the front end).
 #include <math.h>
+#include <stdlib.h>
 
 #include "af_internal.h"
 #include "row_prologue.h"
@@ -664,7 +665,10 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
     a.W = w->Wo; a.scales = (const half_t*)w->So; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;
     if ((rc = gemv(1, 1, a, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
   }
-  {
+  // The router runs inside the gate|up launch when that kernel can take it (fp16 weights, up
+  // to 8 experts, d <= 8192); otherwise as a launch of its own in front of it.
+  const bool fuse_router = !q4 && mcfg->n_experts <= 8 && d <= 8192 && !getenv("AF_MOE_ROUTER_KERNEL");
+  if (!fuse_router) {
     RouterParams rp{};
     rp.rows.pro = AF_PRO_RMSNORM;
     rp.rows.src = hmid;
@@ -692,6 +696,14 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
     a.W = w->Wgateup; a.scales = (const half_t*)w->Sgateup; a.in = d; a.out = top * 2 * f; a.ld = 2 * f; a.y = gu;
     a.w_sel = route->experts; a.n_slots = top;
     bank(a, d, 2 * f);
+    if (fuse_router) {
+      a.router_Wr = (const half_t*)w->Wr;
+      a.router_E = mcfg->n_experts;
+      a.router_top = top;
+      a.router_experts = route->experts;
+      a.router_weights = route->weights;
+      a.router_logits = route->logits;
+    }
     if ((rc = gemv(2, 2, a, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2))) return rc;
   }
   for (int s = 0; s < top; ++s) {

@@ -19,6 +19,11 @@ struct RowPrologue {
     unsigned wave_tot[WAVES];
     float red[WAVES];
     unsigned digit, above;
+    // router of a mixture-of-experts block run inside the gate|up launch
+    float rpart[WAVES][AF_MOE_MAX_EXPERTS];
+    float logit[AF_MOE_MAX_EXPERTS];
+    int experts[AF_MOE_MAX_TOP];
+    float weights[AF_MOE_MAX_TOP];
   };
 
   // Histogram scratch: RP_HIST_COPIES replicas, replica-major (replica r of bin b at
@@ -328,7 +333,15 @@ struct RowPrologue {
       for (int i = tid; i < nv; i += THREADS) dst[vs0 + i] = xv[i];
     }
 
-    // count, scan, list: every thread owns a contiguous run of the range's vectors
+    return range_list(r, xs, sm, list, vs0, nv);
+  }
+
+  // Threshold compare, scan and list over nv vectors of x that lie in LDS at xs; the first of
+  // them is vector vs0 of the operator input.  Every thread owns a contiguous run.
+  static __device__ __forceinline__ int range_list(const af_row_src& r, const unsigned short* xs,
+                                                   Smem& sm, unsigned* list, int vs0, int nv) {
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const int tid = threadIdx.x;
     const int T = threshold_key(r.t);
     const int cv = (nv + THREADS - 1) / THREADS;
     const int v0 = min(tid * cv, nv), v1 = min(v0 + cv, nv);
@@ -360,6 +373,72 @@ struct RowPrologue {
     }
     __syncthreads();
     return (int)tot;
+  }
+
+  // Threshold selection of split s's channel range when the whole x already lies in LDS (the
+  // router below needs all of it): the compare / scan / list part of threshold_range alone.
+  static __device__ __forceinline__ int threshold_range_of_full(const af_row_src& r,
+                                                                const unsigned short* xs, Smem& sm,
+                                                                unsigned* list, int S, int s) {
+    const int nvec = r.n >> 3;
+    const int V = (nvec + S - 1) / S;
+    const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec);
+    return range_list(r, xs + (size_t)vs0 * 8, sm, list, vs0, vs1 - vs0);
+  }
+
+  // The `top` largest of E logits (ties to the lower expert, slot 0 the largest) and the
+  // softmax over them; one thread.
+  static __device__ __forceinline__ void router_pick(const float* logit, int E, int top, int* experts,
+                                                     float* weights) {
+    unsigned taken = 0;
+    float z0 = 0.f, den = 0.f;
+    for (int s = 0; s < top; ++s) {
+      int best = -1;
+      for (int e = 0; e < E; ++e)
+        if (!((taken >> e) & 1u) && (best < 0 || logit[e] > logit[best])) best = e;
+      taken |= 1u << best;
+      experts[s] = best;
+      if (s == 0) z0 = logit[best];
+      weights[s] = expf(logit[best] - z0);
+      den += weights[s];
+    }
+    for (int s = 0; s < top; ++s) weights[s] /= den;
+  }
+
+  // Router of a mixture-of-experts block inside the GEMV's front end: logits[e] = Wr[e] . x over
+  // the x in LDS (n <= 8 * THREADS; wr[e] holds this thread's 8 router weights of expert e,
+  // fetched by the caller before x was built), reduced lanes -> waves -> one lane per expert in a
+  // fixed order, then the pick.  Leaves sm.experts / sm.weights / sm.logit for every thread.
+  template <int E_MAX>
+  static __device__ __forceinline__ void router_in_lds(const unsigned short* xs, int n, Smem& sm,
+                                                       const half8 (&wr)[E_MAX], int E, int top) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const half8* xv = reinterpret_cast<const half8*>(xs);
+    float acc[E_MAX];
+#pragma unroll
+    for (int e = 0; e < E_MAX; ++e) acc[e] = 0.f;
+    if (tid < (n >> 3)) {
+      const half8 x8 = xv[tid];
+#pragma unroll
+      for (int e = 0; e < E_MAX; ++e)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[e] += (float)wr[e][c] * (float)x8[c];
+    }
+#pragma unroll
+    for (int e = 0; e < E_MAX; ++e) {
+      const float t = af_wave_sum(acc[e]);
+      if (lane == 0) sm.rpart[wave][e] = t;
+    }
+    __syncthreads();
+    if (tid < E) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) t += sm.rpart[w][tid];
+      sm.logit[tid] = t;
+    }
+    __syncthreads();
+    if (tid == 0) router_pick(sm.logit, E, top, sm.experts, sm.weights);
+    __syncthreads();
   }
 
   // Select on xs[0..n) (n % 8 == 0) and keep the entries of split s of S in list[] as
