@@ -36,6 +36,12 @@ struct Q4Params {
   const int* w_sel;
   long long w_stride, s_stride;
   const float* y_scale;
+  // in-kernel router of a mixture-of-experts block, as in the fp16 kernel
+  const half_t* router_Wr;
+  int router_E, router_top;
+  int32_t* router_experts;
+  float* router_weights;
+  float* router_logits;
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
@@ -70,7 +76,7 @@ __device__ __forceinline__ void q4_fma8(float* acc, unsigned w, float x, float x
 
 // CL = false: scales [in/32][ld], one per (group of 32 input channels, column);
 // CL = true:  scales [in][ld/32], one per (input channel, group of 32 columns).
-template <int LX, int U, int NW, bool CL>
+template <int LX, int U, int NW, bool CL, bool ROUTED>
 __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   constexpr int THREADS = NW * AF_WAVE;
   constexpr int LY = AF_WAVE / LX;
@@ -96,9 +102,31 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   const int slot = wave * LY + ly;
   const af_row_src& r = p.rows;
 
-  if (p.use_lds_x && !p.range_sel)
+  constexpr int RE = 8;  // experts the in-kernel router handles
+  constexpr bool routed = ROUTED;
+  half8 wr[routed ? RE : 1];
+  if constexpr (routed) {  // this thread's router weights do not depend on x: fetch them first
+#pragma unroll
+    for (int e = 0; e < RE; ++e) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) wr[e][c] = (half_t)0;
+      if (e < p.router_E && tid < (r.n >> 3))
+        wr[e] = *reinterpret_cast<const half8*>(p.router_Wr + (size_t)e * r.n + (size_t)tid * 8);
+    }
+  }
+  if (p.use_lds_x && (!p.range_sel || routed))
     RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
                 r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
+  if constexpr (routed) {
+    RP::template router_in_lds<RE>(xs, r.n, s_rp, wr, p.router_E, p.router_top);
+    if (blockIdx.x == 0 && s == 0) {
+      if (tid < p.router_top) {
+        p.router_experts[tid] = s_rp.experts[tid];
+        p.router_weights[tid] = s_rp.weights[tid];
+      }
+      if (tid < p.router_E) p.router_logits[tid] = s_rp.logit[tid];
+    }
+  }
 
   float yacc[8], acc[8];
 #pragma unroll
@@ -110,8 +138,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   const size_t row_bytes = (size_t)(p.ld / 2);
   const unsigned char* wcol = p.packed + col_ld / 2;
   const half_t* sbase = p.scales;
-  if (p.w_sel) {
-    const int e_sel = p.w_sel[slot_o];
+  if (routed || p.w_sel) {
+    const int e_sel = routed ? s_rp.experts[slot_o] : p.w_sel[slot_o];
     wcol += (size_t)e_sel * (size_t)p.w_stride;
     sbase += (size_t)e_sel * (size_t)p.s_stride;
   }
@@ -205,7 +233,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   };
 
   if (p.range_sel) {
-    stream(RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
+    stream(routed ? RP::threshold_range_of_full(r, xs, s_rp, s_list, S, s)
+                  : RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
   } else if (r.sel != AF_ROWS_GIVEN) {
     int nidx_total;
     const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
@@ -277,29 +306,34 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
-template <int LX, int NW, bool CL>
+template <int LX, int NW, bool CL, bool ROUTED>
 static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW, CL>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW, CL, ROUTED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW, CL>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW, CL, ROUTED>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
 
 template <int LX>
 static void q4_launch_lx(int nw, bool cl, dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
-  if (nw == 16) {
+  if (p.router_Wr != nullptr) {  // the launcher has made sure of nw == 16
     if (cl)
-      q4_launch_one<LX, 16, true>(grid, lds, st, p);
+      q4_launch_one<LX, 16, true, true>(grid, lds, st, p);
     else
-      q4_launch_one<LX, 16, false>(grid, lds, st, p);
+      q4_launch_one<LX, 16, false, true>(grid, lds, st, p);
+  } else if (nw == 16) {
+    if (cl)
+      q4_launch_one<LX, 16, true, false>(grid, lds, st, p);
+    else
+      q4_launch_one<LX, 16, false, false>(grid, lds, st, p);
   } else {
     if (cl)
-      q4_launch_one<LX, 4, true>(grid, lds, st, p);
+      q4_launch_one<LX, 4, true, false>(grid, lds, st, p);
     else
-      q4_launch_one<LX, 4, false>(grid, lds, st, p);
+      q4_launch_one<LX, 4, false, false>(grid, lds, st, p);
   }
 }
 
@@ -346,7 +380,10 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   int list_cap;
   // the split partial sums have to fit the workspace, the staged rows of a split the LDS
   while (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) --S;
-  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, Q4_LIST, &S, &xs_bytes, &list_cap))
+  if (a.router_Wr && (r.pro != AF_PRO_RMSNORM || a.router_E > 8 || r.n > 8192 || nw != 16 || !use_lds_x))
+    return AF_EINVAL;  // the in-kernel router's preconditions (the caller falls back to the router kernel)
+  if (!af_plan_gemv_lds(r, max_rows, use_lds_x, range_sel, Q4_LIST, &S, &xs_bytes, &list_cap,
+                        a.router_Wr != nullptr))
     return AF_EWORKSPACE;
   if (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) return AF_EWORKSPACE;
   Q4Params p;
@@ -370,6 +407,12 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   p.w_stride = a.w_stride;      // bytes of packed nibbles per matrix
   p.s_stride = a.w_stride_scales;  // scale elements per matrix
   p.y_scale = a.y_scale;
+  p.router_Wr = a.router_Wr;
+  p.router_E = a.router_E;
+  p.router_top = a.router_top;
+  p.router_experts = a.router_experts;
+  p.router_weights = a.router_weights;
+  p.router_logits = a.router_logits;
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

@@ -665,9 +665,9 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
     a.W = w->Wo; a.scales = (const half_t*)w->So; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;
     if ((rc = gemv(1, 1, a, AF_PRO_NONE, attn, nullptr, nullptr))) return rc;
   }
-  // The router runs inside the gate|up launch when that kernel can take it (fp16 weights, up
-  // to 8 experts, d <= 8192); otherwise as a launch of its own in front of it.
-  const bool fuse_router = !q4 && mcfg->n_experts <= 8 && d <= 8192 && !getenv("AF_MOE_ROUTER_KERNEL");
+  // The router runs inside the gate|up launch when that kernel can take it (up to 8 experts,
+  // d <= 8192); otherwise as a launch of its own in front of it.
+  const bool fuse_router = mcfg->n_experts <= 8 && d <= 8192 && !getenv("AF_MOE_ROUTER_KERNEL");
   if (!fuse_router) {
     RouterParams rp{};
     rp.rows.pro = AF_PRO_RMSNORM;

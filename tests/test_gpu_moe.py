@@ -202,3 +202,24 @@ def test_moe_other_top_counts(ctx, top):
     same = all(np.array_equal(to_host(lay.idx[p])[: ks[p]], tr.idx[p]) for p in range(3))
     same &= all(np.array_equal(to_host(lay.idx[3 + s])[: ks[3]], tr.idx_down[s]) for s in range(top))
     assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
+
+
+def test_router_as_its_own_launch_gives_the_same_layer(ctx, monkeypatch):
+    """The router runs inside the gate|up launch by default; the stand-alone router kernel (used
+    when that launch cannot take it) must lead to the same experts and the same layer output."""
+    shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 11)
+    ks = tuple(O.keep_count(n, 50) for n in widths)
+    lay = M.DeviceMoeLayer(ctx, shape, w)
+    hin = to_dev(h)
+    outs = []
+    for separate in (False, True):
+        if separate:
+            monkeypatch.setenv("AF_MOE_ROUTER_KERNEL", "1")
+        hout = torch.zeros_like(hin)
+        lay.run(hin, hout, to_dev(K), to_dev(V), KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
+        ctx.synchronize()
+        outs.append((to_host(lay.experts).copy(), to_host(lay.weights).copy(), to_host(lay.logits).copy(),
+                     to_host(hout).copy()))
+    assert outs[0][0].tolist() == outs[1][0].tolist()
+    assert np.allclose(outs[0][1], outs[1][1], rtol=1e-5) and np.allclose(outs[0][2], outs[1][2], rtol=1e-4, atol=1e-5)
+    assert O.rel_err(outs[0][3], outs[1][3], 1.0) <= 1e-3
