@@ -42,7 +42,8 @@ typedef enum {
   AF_ENULL = -2,      /* a required pointer is NULL                           */
   AF_ESHAPE = -3,     /* a dimension violates the layout rules stated below   */
   AF_EWORKSPACE = -4, /* no workspace set, or it is too small for this call   */
-  AF_EHIP = -5        /* the HIP runtime reported an error (launch, stream)   */
+  AF_EHIP = -5,       /* the HIP runtime reported an error (launch, stream)   */
+  AF_ENOALLOC_LIMIT = -6 /* af_sparse_gemv_f16_noalloc: out exceeds AF_NOALLOC_MAX_OUT */
 } af_status;
 
 enum { AF_F16 = 0, AF_F32 = 1 };                              /* y_kind            */
@@ -124,6 +125,25 @@ int af_sparse_gemv_q4(af_ctx* ctx, const void* packed, const void* scales_f16, i
 int af_sparse_gemv_q4_cl(af_ctx* ctx, const void* packed, const void* scales_f16, int in, int out,
                       int ld, const void* x_f16, const int32_t* idx, int nidx_host,
                       const int32_t* nidx_dev, void* y, int y_kind, const void* residual_f16);
+
+/* The same operation for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same kernels and same results as af_sparse_gemv_f16, but the tickets and split
+ * partial sums live in a device array that is part of the library image (about 4.03 MB on every
+ * GPU that loads the library, held until the process ends) instead of the workspace, and the
+ * call allocates nothing.  The context needs no workspace; its device must be the current HIP
+ * device (else AF_EINVAL).  Limits: in <= AF_MAX_N, out <= AF_NOALLOC_MAX_OUT (beyond that:
+ * AF_ENOALLOC_LIMIT, nothing launched).  The array keeps the last call's contents; the call
+ * clears the counters it needs with a fill kernel on the context's stream before the GEMV.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams,
+ * different contexts or processes do not matter: the array is per process and GPU) race; issue
+ * them on one stream or order them with events.  The first call on a device looks the array's
+ * address up (no allocation, no stream work). */
+enum { AF_NOALLOC_MAX_OUT = 65536 };
+int af_sparse_gemv_f16_noalloc(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                               const void* x_f16, const int32_t* idx, int nidx_host,
+                               const int32_t* nidx_dev, void* y, int y_kind,
+                               const void* residual_f16);
 
 /* ---- fused front end: operations T and C of Section 4 in one launch --------------------
  * The GEMV kernel builds its own input vector and selects on it, so no activation or index

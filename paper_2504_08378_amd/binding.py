@@ -22,6 +22,7 @@ AF_SEL_SKIP_SETS = 1
 AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
 AF_CALIB_BINS = 32768
+AF_NOALLOC_MAX_OUT, AF_ENOALLOC_LIMIT = 65536, -6
 
 EXPORTS = [
     "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
@@ -32,7 +33,7 @@ EXPORTS = [
     "af_calib_accumulate", "af_calib_accumulate_layer", "af_calib_thresholds",
     "af_decode_moe_layer", "af_select_gemv_experts_f16",
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
-    "af_cost_eval", "af_plan_search",
+    "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -130,6 +131,7 @@ def lib() -> C.CDLL:
         "af_pack_inmajor_f16": (i, [vp, vp, i, i, vp, i, i]),
         "af_pack_q4_g32": (i, [vp, vp, i, i, vp, vp, i, i]),
         "af_sparse_gemv_f16": (i, [vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
+        "af_sparse_gemv_f16_noalloc": (i, [vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
         "af_sparse_gemv_q4": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
         "af_sparse_gemv_q4_cl": (i, [vp, vp, vp, i, i, i, vp, vp, i, vp, vp, i, vp]),
         "af_pack_q4_cl": (i, [vp, vp, i, i, vp, vp, i, i]),
@@ -197,7 +199,8 @@ class Context:
     """One af_ctx bound to a device and a torch stream, with its workspace tensor."""
 
     def __init__(self, device: int = 0, stream: torch.cuda.Stream | None = None,
-                 max_in: int = AF_MAX_N, max_out: int = 65536, max_batch: int = AF_MAX_BATCH):
+                 max_in: int = AF_MAX_N, max_out: int = 65536, max_batch: int = AF_MAX_BATCH,
+                 with_workspace: bool = True):
         L = lib()
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the active-weight path has no CPU fallback")
@@ -206,6 +209,10 @@ class Context:
         h = C.c_void_p()
         _check(L.af_create(C.byref(h), device, C.c_void_p(self.stream.cuda_stream)), "af_create")
         self._h = h
+        self.workspace = None
+        self.max_in, self.max_out, self.max_batch = max_in, max_out, max_batch
+        if not with_workspace:   # only the entry points that bring their own scratch work then
+            return
         nbytes = L.af_workspace_bytes(max_in, max_out, max_batch)
         if nbytes == 0:
             raise ValueError("invalid workspace limits")
@@ -303,6 +310,25 @@ class Context:
             _ptr(idx, torch.int32, "idx"), int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"),
             _ptr(y, None, "y"), y_kind, _ptr(residual, torch.float16, "residual")),
             "af_sparse_gemv_f16")
+        return y
+
+    def sparse_gemv_f16_noalloc(self, Wt, x, idx=None, nidx=None, nidx_dev=None, y=None,
+                                y_kind=AF_F16, residual=None, out=None):
+        """af_sparse_gemv_f16_noalloc: y must be given by callers that may not allocate; when it
+        is omitted here the output tensor is made before the call, the call itself allocates
+        nothing."""
+        n_in, ld = Wt.shape
+        out = ld if out is None else out
+        if y is None:
+            y = torch.empty(out, dtype=torch.float16 if y_kind == AF_F16 else torch.float32,
+                            device=self.device)
+        if idx is not None and nidx is None:
+            nidx = idx.numel()
+        _check(lib().af_sparse_gemv_f16_noalloc(
+            self._h, _ptr(Wt, torch.float16, "Wt"), n_in, out, ld, _ptr(x, torch.float16, "x"),
+            _ptr(idx, torch.int32, "idx"), int(nidx or 0), _ptr(nidx_dev, torch.int32, "nidx_dev"),
+            _ptr(y, None, "y"), y_kind, _ptr(residual, torch.float16, "residual")),
+            "af_sparse_gemv_f16_noalloc")
         return y
 
     def sparse_gemv_q4(self, packed, scales, x, idx=None, nidx=None, nidx_dev=None, y=None,

@@ -69,6 +69,7 @@ extern "C" const char* af_strerror(int status) {
     case AF_ESHAPE: return "dimension violates the layout rules";
     case AF_EWORKSPACE: return "workspace missing or too small";
     case AF_EHIP: return "HIP runtime error";
+    case AF_ENOALLOC_LIMIT: return "size beyond the limit of the allocation-free entry point";
     default: return "unknown status";
   }
 }

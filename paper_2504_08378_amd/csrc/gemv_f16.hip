@@ -405,21 +405,28 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   return AF_OK;
 }
 
-extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
-                                  const void* x_f16, const int32_t* idx, int nidx_host,
-                                  const int32_t* nidx_dev, void* y, int y_kind,
-                                  const void* residual_f16) {
+// Argument checks of af_sparse_gemv_f16 (nothing is launched), and the launch itself.
+static int sparse_gemv_f16_check(const af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                 const void* x_f16, const int32_t* idx, int* nidx_host,
+                                 const int32_t** nidx_dev, const void* y, int y_kind) {
   if (!ctx || !Wt || !x_f16 || !y) return AF_ENULL;
   if (in <= 0 || out <= 0 || in > AF_MAX_N) return AF_EINVAL;
   if (out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
   if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
   if (idx == nullptr) {
-    nidx_host = in;
-    nidx_dev = nullptr;
+    *nidx_host = in;
+    *nidx_dev = nullptr;
   }
-  if (nidx_host < 0 || nidx_host > in) return AF_EINVAL;
+  if (*nidx_host < 0 || *nidx_host > in) return AF_EINVAL;
   if (!ctx->ws) return AF_EWORKSPACE;
   if (in > ctx->max_in || out > ctx->max_out) return AF_EWORKSPACE;
+  return AF_OK;
+}
+
+static int sparse_gemv_f16_launch(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                  const void* x_f16, const int32_t* idx, int nidx_host,
+                                  const int32_t* nidx_dev, void* y, int y_kind,
+                                  const void* residual_f16) {
   af_gemv_args a{};
   a.W = Wt;
   a.in = in;
@@ -436,6 +443,71 @@ extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;
   return af_launch_gemv_f16(ctx, a);
+}
+
+extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                  const void* x_f16, const int32_t* idx, int nidx_host,
+                                  const int32_t* nidx_dev, void* y, int y_kind,
+                                  const void* residual_f16) {
+  const int rc = sparse_gemv_f16_check(ctx, Wt, in, out, ld, x_f16, idx, &nidx_host, &nidx_dev, y, y_kind);
+  if (rc) return rc;
+  return sparse_gemv_f16_launch(ctx, Wt, in, out, ld, x_f16, idx, nidx_host, nidx_dev, y, y_kind,
+                                residual_f16);
+}
+
+// ---- the same operation for callers that cannot allocate ---------------------------------
+// The tickets and split partials live in a device array of the library image instead of the
+// caller's workspace.  Every GPU that loads the library holds its own copy of the array at its
+// own address; the name below is only the host-side handle of the symbol, the address comes
+// from hipGetSymbolAddress once per device.
+#define AF_NOALLOC_PARTIAL_FLOATS (1u << 20)
+#define AF_NOALLOC_BYTES (sizeof(int) * AF_N_TICKETS + sizeof(float) * AF_NOALLOC_PARTIAL_FLOATS)
+#define AF_NOALLOC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[AF_NOALLOC_BYTES];
+static void* g_scratch_ptr[AF_NOALLOC_MAX_DEVICES];  // per device, filled on first use
+
+__global__ void noalloc_clear_kernel(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+extern "C" int af_sparse_gemv_f16_noalloc(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                          const void* x_f16, const int32_t* idx, int nidx_host,
+                                          const int32_t* nidx_dev, void* y, int y_kind,
+                                          const void* residual_f16) {
+  if (!ctx) return AF_ENULL;
+  if (out > AF_NOALLOC_MAX_OUT) return AF_ENOALLOC_LIMIT;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return AF_EHIP;
+  if (dev != ctx->device || dev < 0 || dev >= AF_NOALLOC_MAX_DEVICES) return AF_EINVAL;
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return AF_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  char* base = (char*)g_scratch_ptr[dev];
+  // a shallow copy of the context whose scratch is the device array: same stream, same device
+  af_ctx local = *ctx;
+  local.ws = base;
+  local.ws_bytes = AF_NOALLOC_BYTES;
+  local.max_in = AF_MAX_N;
+  local.max_out = AF_NOALLOC_MAX_OUT;
+  local.max_batch = 1;
+  local.lay = af_ws_layout{};
+  local.lay.tickets = 0;
+  local.lay.partials = sizeof(int) * AF_N_TICKETS;
+  local.lay.partial_floats = AF_NOALLOC_PARTIAL_FLOATS;
+  local.lay.total = AF_NOALLOC_BYTES;
+  const int rc = sparse_gemv_f16_check(&local, Wt, in, out, ld, x_f16, idx, &nidx_host, &nidx_dev, y, y_kind);
+  if (rc) return rc;
+  // The array keeps what the last call left.  A completed call leaves its tickets at zero, but
+  // a call that was cut short does not, so the tickets are cleared in front of every launch
+  // (a fill kernel, not a memset node: the call may be under stream capture).
+  hipLaunchKernelGGL(noalloc_clear_kernel, dim3(AF_TICKET_ATTN / 256), dim3(256), 0, ctx->stream,
+                     (int*)base, (int)AF_TICKET_ATTN);
+  AF_LAUNCH_CHECK();
+  return sparse_gemv_f16_launch(&local, Wt, in, out, ld, x_f16, idx, nidx_host, nidx_dev, y,
+                                y_kind, residual_f16);
 }
 
 static int select_gemv_any(af_ctx* ctx, const int32_t* expert_sel, int n_slots,
