@@ -483,6 +483,20 @@ def main() -> int:
     ms_per_step = dt / args.steps * 1e3
     tok_s = args.steps / dt
 
+    # ---- spread of the step time: one event pair per step on the library's stream ----------
+    n_ev = max(20, min(args.steps, 400))
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
+    evs[0].record(ctx.stream)
+    for i in range(n_ev):
+        step()
+        evs[i + 1].record(ctx.stream)
+    ctx.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_ev))
+    pct = lambda q: per_step[min(n_ev - 1, int(q * n_ev))]
+    step_ms = {"n": n_ev, "median": round(pct(0.5), 4), "p10": round(pct(0.1), 4), "p90": round(pct(0.9), 4),
+               "min": round(per_step[0], 4), "max": round(per_step[-1], 4),
+               "note": "event pair per step; the events add a little to each step"}
+
     # active weight bytes of one token (the four operators of every layer)
     bpw = 2.0 if kind == B.AF_W_F16 else 0.5
     outs = (shape.qkv_out, shape.d_model, 2 * shape.d_ffn, shape.d_model)
@@ -492,6 +506,67 @@ def main() -> int:
         active_bytes += L * sum(widths[p] // 32 * outs[p] for p in range(4)) * 2
     elif kind == B.AF_W_Q4CL:  # a channel's scales travel with its nibbles
         active_bytes += sum(rows[l][p] * (outs[p] // 32) * 2 for l in range(L) for p in range(4))
+
+    # ---- every operator of the step, in place: device time stamps written by the kernels ---
+    per_op = None
+    khz = ctx.wall_clock_khz()
+    if graph is not None and khz > 0 and args.group == 1:
+        n_ops = 5 * L
+        stamps = torch.empty((n_ops, 2), dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        ctx.profile_set(stamps)
+        ctx.capture_begin()
+        run()
+        graph_prof = ctx.capture_end()
+        ctx.profile_set(None)
+        samples = []
+        for _ in range(12):
+            stamps[:, 0] = torch.iinfo(torch.int64).max
+            stamps[:, 1] = 0
+            torch.cuda.synchronize()
+            ctx.graph_launch(graph_prof)
+            ctx.synchronize()
+            samples.append(stamps.cpu().numpy().astype(np.int64))
+        ctx.graph_destroy(graph_prof)
+        samples = np.stack(samples[2:])                     # [rep, launch, 2]
+        tick_us = 1e3 / khz
+        busy = (samples[:, :, 1] - samples[:, :, 0]) * tick_us                      # entry -> exit
+        nxt = np.concatenate([samples[:, 1:, 0], samples[:, -1:, 1]], axis=1)
+        pitch = (nxt - samples[:, :, 0]) * tick_us                                  # entry -> next entry
+        names = ("qkv", "attention", "o", "gate|up", "down")
+        if keep_frac is None:
+            rows_l = [list(ks)] * L
+        else:
+            rows_l = kept
+        kvb = 2 * (kv_len + 1) * shape.n_kv_heads * shape.head_dim * 2             # K and V read by attention
+        d_, f_ = shape.d_model, shape.d_ffn
+
+        def op_bytes(l, o):
+            r4 = rows_l[l]
+            if kind != B.AF_W_F16:
+                wb = lambda k_, n_in, out_: k_ * (out_ // 2 + 6) + out_ * 2 + (
+                    (n_in // 32) * out_ * 2 if kind == B.AF_W_Q4G32 else k_ * (out_ // 32) * 2)
+            else:
+                wb = lambda k_, n_in, out_: k_ * (out_ * 2 + 6) + out_ * 2
+            if o == 0:
+                return wb(r4[0], d_, shape.qkv_out) + 2 * d_ * 2
+            if o == 1:
+                return kvb + shape.qkv_out * 2 + widths[1] * 2
+            if o == 2:
+                return wb(r4[1], widths[1], d_) + d_ * 2
+            if o == 3:
+                return wb(r4[2], d_, 2 * f_) + 2 * d_ * 2
+            return wb(r4[3], f_, d_) + d_ * 2 + 2 * f_ * 2
+        per_op = []
+        for o, nm in enumerate(names):
+            sel_ = np.arange(o, n_ops, 5)
+            us_busy = float(np.median(busy[:, sel_].mean(axis=1)))
+            us_pitch = float(np.median(pitch[:, sel_].mean(axis=1)))
+            byts = float(np.mean([op_bytes(l, o) for l in range(L)]))
+            per_op.append({"op": nm, "us": round(us_busy, 2), "us_to_next_start": round(us_pitch, 2),
+                           "bytes": int(byts), "GBps": round(byts / us_pitch / 1e3, 1),
+                           "frac_of_hbm_peak": round(byts / us_pitch / 1e3 / HBM_PEAK_GBPS, 4)})
+        per_op_sum_us = round(sum(p_["us_to_next_start"] for p_ in per_op) * L, 1)
 
     # ---- roofline of the dominant kernel ------------------------------------------------
     # The gate|up operator as it runs inside the step: one launch that builds
@@ -724,9 +799,17 @@ def main() -> int:
         "active_weight_GBps": round(active_bytes * tok_s / 1e9, 1),
         "active_weight_frac_of_hbm_peak": round(active_bytes * tok_s / 1e9 / HBM_PEAK_GBPS, 4),
         "build_s": round(t_build, 1),
+        "step_ms": step_ms,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if per_op is not None:
+        out["per_op"] = per_op
+        out["per_op_note"] = ("mean over the layers of one graph replay, median over 10 replays; us = first "
+                              "workgroup entry to last workgroup exit by the device wall clock, "
+                              "us_to_next_start = entry to the next kernel's entry (sums to the step: "
+                              f"{per_op_sum_us} us); bytes = algorithmic bytes of the operator (attention: "
+                              "the KV rows it reads); fractions use us_to_next_start")
     if keep_frac is not None:
         out["config"]["kept_fraction_by_point"] = keep_frac
     if lfu is not None:

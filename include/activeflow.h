@@ -389,6 +389,18 @@ int af_probe_sink_floats(af_ctx* ctx);
 int af_probe_stream_read(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
                          int wgs_per_cu);
 
+/* Measurement aid: time stamps of the layer kernels.  While a stamp buffer is set, every kernel
+ * that af_decode_layer / af_decode_stack / af_decode_moe_layer and the GEMV entry points launch
+ * takes the next free slot, in launch order (slot i = int64 pair dev_stamps[2i], [2i+1]); its
+ * workgroups write the earliest kernel entry (atomic min) and the latest exit (atomic max), in
+ * ticks of the device's constant-rate wall clock (hipDeviceAttributeWallClockRate, kHz).  The
+ * caller fills the buffer with INT64_MAX (even entries) and 0 (odd entries) before each run and
+ * reads it after synchronising.  Launches beyond n_slots are not stamped.  af_profile_set
+ * restarts at slot 0; NULL switches the stamps off.  A captured graph keeps the slots it was
+ * recorded with.  dev_stamps: device memory, 8-byte aligned, 2 * n_slots int64. */
+int af_profile_set(af_ctx* ctx, void* dev_stamps, int n_slots);
+int af_wall_clock_khz(af_ctx* ctx); /* tick rate of those stamps; 0 if unknown */
+
 /* Stream capture helpers: record the calls made between begin and end into a HIP graph
  * and replay it.  The graph holds the pointers and scalars of the recorded calls. */
 typedef struct af_graph af_graph;

@@ -34,6 +34,7 @@ EXPORTS = [
     "af_decode_moe_layer", "af_select_gemv_experts_f16",
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
     "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
+    "af_profile_set", "af_wall_clock_khz",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -160,6 +161,8 @@ def lib() -> C.CDLL:
                             C.POINTER(i)]),
         "af_lfu_stats": (i, [vp] + [C.POINTER(C.c_longlong)] * 4),
         "af_lfu_cached": (i, [vp, C.POINTER(C.c_int32), C.POINTER(i)]),
+        "af_profile_set": (i, [vp, vp, i]),
+        "af_wall_clock_khz": (i, [vp]),
         "af_cost_eval": (i, [C.POINTER(CostIn), C.POINTER(CostOut)]),
         "af_plan_search": (i, [C.POINTER(PlanIn), C.POINTER(PlanOut)]),
         "af_decode_moe_layer": (i, [vp, C.POINTER(MoeCfg), C.POINTER(MoeWeights), vp, vp, vp, vp,
@@ -490,6 +493,17 @@ class Context:
         return out
 
     # ---- measurement -----------------------------------------------------------------
+    def profile_set(self, stamps=None):
+        """stamps: int64 CUDA tensor [n_slots, 2] (entry min, exit max per launch), or None."""
+        if stamps is None:
+            _check(lib().af_profile_set(self._h, None, 0), "af_profile_set")
+        else:
+            _check(lib().af_profile_set(self._h, _ptr(stamps, torch.int64, "stamps"),
+                                        stamps.numel() // 2), "af_profile_set")
+
+    def wall_clock_khz(self) -> int:
+        return int(lib().af_wall_clock_khz(self._h))
+
     def probe_sink(self):
         return torch.zeros(lib().af_probe_sink_floats(self._h), dtype=torch.float32,
                            device=self.device)

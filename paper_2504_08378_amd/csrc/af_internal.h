@@ -35,7 +35,16 @@ struct af_ctx {
   int max_in, max_out, max_batch;
   af_ws_layout lay;
   int n_cu;
+  // af_profile_set: device stamps [2 * prof_slots], next slot to hand to a layer kernel
+  long long* prof;
+  int prof_slots, prof_next;
 };
+
+// Slot of the next layer kernel's time stamps (null: profiling off or slots used up).
+static inline long long* af_prof_take(af_ctx* ctx) {
+  if (!ctx->prof || ctx->prof_next >= ctx->prof_slots) return nullptr;
+  return ctx->prof + 2 * (size_t)(ctx->prof_next++);
+}
 
 struct af_graph {
   hipGraph_t graph;
@@ -181,6 +190,15 @@ __device__ __forceinline__ int af_ticket_take(int* t) {
 #endif
 
 #ifdef __HIPCC__
+// Time stamps of a layer kernel (af_profile_set): slot[0] = earliest entry, slot[1] = latest
+// exit over its workgroups, in ticks of the device's constant-rate wall clock.
+__device__ __forceinline__ void af_prof_begin(long long* slot) {
+  if (slot && threadIdx.x == 0) atomicMin((unsigned long long*)slot, (unsigned long long)wall_clock64());
+}
+__device__ __forceinline__ void af_prof_end(long long* slot) {
+  if (slot && threadIdx.x == 0) atomicMax((unsigned long long*)slot + 1, (unsigned long long)wall_clock64());
+}
+
 // ---- wave64 scans and sums on the DPP data path ------------------------------------------
 // Inclusive prefix sum over the 64 lanes of a wave: four row_shr steps scan each row of 16
 // lanes (lanes shifted in from outside the row read 0), row_bcast:15 adds a row's total to

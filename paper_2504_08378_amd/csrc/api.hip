@@ -55,6 +55,23 @@ extern "C" int af_destroy(af_ctx* ctx) {
   return AF_OK;
 }
 
+extern "C" int af_profile_set(af_ctx* ctx, void* dev_stamps, int n_slots) {
+  if (!ctx) return AF_ENULL;
+  if (dev_stamps != nullptr && n_slots <= 0) return AF_EINVAL;
+  if ((uintptr_t)dev_stamps & 7u) return AF_ESHAPE;
+  ctx->prof = (long long*)dev_stamps;
+  ctx->prof_slots = dev_stamps ? n_slots : 0;
+  ctx->prof_next = 0;
+  return AF_OK;
+}
+
+extern "C" int af_wall_clock_khz(af_ctx* ctx) {
+  if (!ctx) return 0;
+  int khz = 0;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, ctx->device) != hipSuccess) return 0;
+  return khz;
+}
+
 extern "C" int af_set_stream(af_ctx* ctx, void* hip_stream) {
   if (!ctx) return AF_ENULL;
   ctx->stream = (hipStream_t)hip_stream;

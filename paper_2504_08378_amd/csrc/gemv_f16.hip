@@ -52,6 +52,7 @@ struct GemvParams {
   int32_t* router_experts;
   float* router_weights;
   float* router_logits;
+  long long* prof;  // time stamps of this launch (af_profile_set), or null
 };
 
 __device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
@@ -82,6 +83,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
   // staged rows, (index << 16 | fp16 bits of x)
   unsigned* s_list = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(xs) + p.list_off);
 
+  af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
   const int slot = blockIdx.x / p.tiles_per_slot;
@@ -247,6 +249,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
       for (int w = 0; w < GEMV_WAVES; ++w) v += s_red[w][c];
       store_out(p, out0 + c, v);
     }
+    af_prof_end(p.prof);
     return;
   }
 
@@ -264,10 +267,14 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
     s_last = (old == S - 1);
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!s_last) {
+    af_prof_end(p.prof);
+    return;
+  }
   for (int c = tid; c < valid; c += GEMV_THREADS)
     store_out(p, out0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
+  af_prof_end(p.prof);
 }
 
 // Tile width, waves per workgroup and split count for a shape.  AF_GEMV_LX / AF_GEMV_NW /
@@ -393,6 +400,7 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.router_experts = a.router_experts;
   p.router_weights = a.router_weights;
   p.router_logits = a.router_logits;
+  p.prof = af_prof_take(ctx);
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

@@ -42,6 +42,7 @@ struct Q4Params {
   int32_t* router_experts;
   float* router_weights;
   float* router_logits;
+  long long* prof;  // time stamps of this launch (af_profile_set), or null
 };
 
 __device__ __forceinline__ void q4_store_out(const Q4Params& p, int col, float v) {
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   // staged rows, (index << 16 | fp16 bits of x)
   unsigned* s_list = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(xs) + p.list_off);
 
+  af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
   const int slot_o = blockIdx.x / p.tiles_per_slot;
@@ -284,6 +286,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
       for (int w = 0; w < NW; ++w) v += s_red[w][c];
       q4_store_out(p, out0 + c, v);
     }
+    af_prof_end(p.prof);
     return;
   }
   float* mine = p.partials + (size_t)s * p.out_pad;
@@ -300,10 +303,14 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
     s_last = (old == S - 1);
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!s_last) {
+    af_prof_end(p.prof);
+    return;
+  }
   for (int c = tid; c < valid; c += THREADS)
     q4_store_out(p, out0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
+  af_prof_end(p.prof);
 }
 
 template <int LX, int NW, bool CL, bool ROUTED>
@@ -413,6 +420,7 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   p.router_experts = a.router_experts;
   p.router_weights = a.router_weights;
   p.router_logits = a.router_logits;
+  p.prof = af_prof_take(ctx);
   const size_t lds = xs_bytes + (size_t)list_cap * 4;
   dim3 grid(tiles, S);
   if (lx == 64)

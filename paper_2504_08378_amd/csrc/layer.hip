@@ -30,6 +30,7 @@ struct AttnParams {
   float* part;         // [n_heads][KS][HD+2]
   int* tickets;        // [n_heads]
   int n_heads, n_kv, kv_len, kv_cap;
+  long long* prof;     // time stamps of this launch (af_profile_set), or null
   float cs[64], sn[64];  // cos / sin of pos * theta^(-2i/HD), i < HD/2, formed in fp64 on the host
 };
 
@@ -46,6 +47,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   __shared__ float s_red[ATT_WAVES];
   __shared__ int s_last;
 
+  af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = blockIdx.x, KS = gridDim.y, s = blockIdx.y;
   const int rep = p.n_heads / p.n_kv, kvh = h / rep;
@@ -198,7 +200,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
       af_store_agent(mine + 2 + tid, v);
     }
   }
-  if (KS == 1) return;
+  if (KS == 1) {
+    af_prof_end(p.prof);
+    return;
+  }
   if (tid == 0) {
     af_store_agent(mine, m);
     af_store_agent(mine + 1, l);
@@ -210,7 +215,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
     s_last = (old == KS - 1);
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!s_last) {
+    af_prof_end(p.prof);
+    return;
+  }
   // combine the splits in split order; loads go out eight splits at a time
   const float* base = p.part + (size_t)h * KS * (HD + 2);
   if (tid < HD) {
@@ -246,6 +254,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
     p.out[(size_t)h * HD + tid] = (half_t)(v / L);
   }
   if (tid == 0) af_ticket_reset(&p.tickets[h]);
+  af_prof_end(p.prof);
 }
 
 static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc,
@@ -266,6 +275,7 @@ static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* 
   p.n_kv = cfg->n_kv_heads;
   p.kv_len = kv_len;
   p.kv_cap = kv_cap;
+  p.prof = af_prof_take(ctx);
   for (int i = 0; i < cfg->head_dim / 2; ++i) {
     const double ang = (double)pos * pow((double)cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
     p.cs[i] = (float)cos(ang);
