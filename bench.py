@@ -369,6 +369,8 @@ def main() -> int:
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--layer-kernel", action="store_true",
+                    help="one launch per layer (AF_OPT_LAYER_KERNEL) instead of one per operator")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); "
@@ -406,6 +408,8 @@ def main() -> int:
     ks = tuple(keep_count(n, sp) for n in widths)
 
     ctx = B.Context(0)
+    if args.layer_kernel:
+        ctx.set_option(B.AF_OPT_LAYER_KERNEL, 1)
     t_build = time.time()
     layers, kv, host_layer0 = [], [], None
     for l in range(L):
@@ -564,8 +568,8 @@ def main() -> int:
             us_pitch = float(np.median(pitch[:, sel_].mean(axis=1)))
             byts = float(np.mean([op_bytes(l, o) for l in range(L)]))
             per_op.append({"op": nm, "us": round(us_busy, 2), "us_to_next_start": round(us_pitch, 2),
-                           "bytes": int(byts), "GBps": round(byts / us_pitch / 1e3, 1),
-                           "frac_of_hbm_peak": round(byts / us_pitch / 1e3 / HBM_PEAK_GBPS, 4)})
+                           "bytes": int(byts), "GBps": round(byts / max(us_pitch, 1e-9) / 1e3, 1),
+                           "frac_of_hbm_peak": round(byts / max(us_pitch, 1e-9) / 1e3 / HBM_PEAK_GBPS, 4)})
         per_op_sum_us = round(sum(p_["us_to_next_start"] for p_ in per_op) * L, 1)
 
     # ---- roofline of the dominant kernel ------------------------------------------------

@@ -60,6 +60,26 @@ int af_destroy(af_ctx* ctx);
 int af_set_stream(af_ctx* ctx, void* hip_stream);
 const char* af_strerror(int status);
 
+/* Options of a context.  AF_OPT_LAYER_KERNEL (default 0): with 1, af_decode_layer /
+ * af_decode_stack run a layer with fp16 weights as ONE launch whose workgroups (one per compute
+ * unit, all resident together) go through the five operators and hand results on through
+ * memory and counters in the workspace, instead of one launch per operator.  Both give the same
+ * results; on the hardware measured the single launch is the slower of the two (a counter
+ * hand-off costs what a kernel boundary costs in a replayed graph), which is why it is off by
+ * default.  It needs the GPU to itself for its duration (another kernel that occupies compute
+ * units only delays it); configurations it does not cover (4-bit weights, more heads than
+ * compute units, very long caches) take the per-operator path by themselves. */
+enum { AF_OPT_LAYER_KERNEL = 1 };
+int af_set_option(af_ctx* ctx, int option, int value);
+
+/* Device error word of the context's workspace (host call; waits for the context's stream):
+ * *flags receives the OR of AF_DEVERR_* bits set by kernels since the word was last cleared;
+ * clear != 0 resets it.  AF_DEVERR_SPIN: a bounded wait inside the single-launch layer kernel
+ * ran out (its results are invalid; set the workspace again before further calls).
+ * AF_DEVERR_IDX: an index list broke its precondition (see af_set_validate). */
+enum { AF_DEVERR_SPIN = 1, AF_DEVERR_IDX = 2 };
+int af_last_device_error(af_ctx* ctx, int* flags, int clear);
+
 /* Scratch memory.  af_workspace_bytes() gives the size that serves every call whose
  * dimensions stay within max_in input channels, max_out output columns (of the widest
  * fused matrix) and max_batch tokens; 0 if an argument is invalid.
@@ -393,9 +413,10 @@ int af_probe_stream_read(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* s
  * that af_decode_layer / af_decode_stack / af_decode_moe_layer and the GEMV entry points launch
  * takes the next free slot, in launch order (slot i = int64 pair dev_stamps[2i], [2i+1]); its
  * workgroups write the earliest kernel entry (atomic min) and the latest exit (atomic max), in
- * ticks of the device's constant-rate wall clock (hipDeviceAttributeWallClockRate, kHz).  The
- * caller fills the buffer with INT64_MAX (even entries) and 0 (odd entries) before each run and
- * reads it after synchronising.  Launches beyond n_slots are not stamped.  af_profile_set
+ * ticks of the device's constant-rate wall clock (hipDeviceAttributeWallClockRate, kHz).  A
+ * phase of the single-launch layer kernel counts as a kernel.  The caller fills the buffer with
+ * INT64_MAX (even entries) and 0 (odd entries) before each run and reads it after
+ * synchronising.  Launches beyond n_slots are not stamped.  af_profile_set
  * restarts at slot 0; NULL switches the stamps off.  A captured graph keeps the slots it was
  * recorded with.  dev_stamps: device memory, 8-byte aligned, 2 * n_slots int64. */
 int af_profile_set(af_ctx* ctx, void* dev_stamps, int n_slots);

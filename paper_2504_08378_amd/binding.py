@@ -23,6 +23,8 @@ AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
 AF_CALIB_BINS = 32768
 AF_NOALLOC_MAX_OUT, AF_ENOALLOC_LIMIT = 65536, -6
+AF_OPT_LAYER_KERNEL = 1
+AF_DEVERR_SPIN, AF_DEVERR_IDX = 1, 2
 
 EXPORTS = [
     "af_create", "af_destroy", "af_set_stream", "af_strerror", "af_workspace_bytes",
@@ -34,7 +36,7 @@ EXPORTS = [
     "af_decode_moe_layer", "af_select_gemv_experts_f16",
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
     "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
-    "af_profile_set", "af_wall_clock_khz",
+    "af_profile_set", "af_wall_clock_khz", "af_set_option", "af_last_device_error",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -163,6 +165,8 @@ def lib() -> C.CDLL:
         "af_lfu_cached": (i, [vp, C.POINTER(C.c_int32), C.POINTER(i)]),
         "af_profile_set": (i, [vp, vp, i]),
         "af_wall_clock_khz": (i, [vp]),
+        "af_set_option": (i, [vp, i, i]),
+        "af_last_device_error": (i, [vp, C.POINTER(i), i]),
         "af_cost_eval": (i, [C.POINTER(CostIn), C.POINTER(CostOut)]),
         "af_plan_search": (i, [C.POINTER(PlanIn), C.POINTER(PlanOut)]),
         "af_decode_moe_layer": (i, [vp, C.POINTER(MoeCfg), C.POINTER(MoeWeights), vp, vp, vp, vp,
@@ -500,6 +504,15 @@ class Context:
         else:
             _check(lib().af_profile_set(self._h, _ptr(stamps, torch.int64, "stamps"),
                                         stamps.numel() // 2), "af_profile_set")
+
+    def set_option(self, option: int, value: int):
+        _check(lib().af_set_option(self._h, option, value), "af_set_option")
+
+    def last_device_error(self, clear: bool = True) -> int:
+        flags = C.c_int(0)
+        _check(lib().af_last_device_error(self._h, C.byref(flags), 1 if clear else 0),
+               "af_last_device_error")
+        return flags.value
 
     def wall_clock_khz(self) -> int:
         return int(lib().af_wall_clock_khz(self._h))

@@ -23,7 +23,13 @@ struct af_ws_layout {
   size_t partial_floats;
   size_t attn_floats;
 };
-enum { AF_N_TICKETS = 8192, AF_TICKET_ATTN = 4096 /* first ticket used by attention */ };
+enum {
+  AF_N_TICKETS = 8192,
+  AF_TICKET_ATTN = 4096,  // first ticket used by attention
+  AF_TICKET_PHASE = 8160, // five phase counters of the whole-layer kernel
+  AF_TICKET_ERR = 8176    // device error word (af_last_device_error)
+};
+
 
 af_ws_layout af_layout(int max_in, int max_out, int max_batch);
 
@@ -38,6 +44,8 @@ struct af_ctx {
   // af_profile_set: device stamps [2 * prof_slots], next slot to hand to a layer kernel
   long long* prof;
   int prof_slots, prof_next;
+  int use_layer_kernel;   // af_set_option(AF_OPT_LAYER_KERNEL, 1): one launch per layer
+  int layer_kernel_state; // 0 not probed yet, 1 usable, -1 not usable on this device
 };
 
 // Slot of the next layer kernel's time stamps (null: profiling off or slots used up).
@@ -198,6 +206,7 @@ __device__ __forceinline__ void af_prof_begin(long long* slot) {
 __device__ __forceinline__ void af_prof_end(long long* slot) {
   if (slot && threadIdx.x == 0) atomicMax((unsigned long long*)slot + 1, (unsigned long long)wall_clock64());
 }
+
 
 // ---- wave64 scans and sums on the DPP data path ------------------------------------------
 // Inclusive prefix sum over the 64 lanes of a wave: four row_shr steps scan each row of 16

@@ -55,6 +55,31 @@ extern "C" int af_destroy(af_ctx* ctx) {
   return AF_OK;
 }
 
+extern "C" int af_set_option(af_ctx* ctx, int option, int value) {
+  if (!ctx) return AF_ENULL;
+  switch (option) {
+    case AF_OPT_LAYER_KERNEL:
+      ctx->use_layer_kernel = value ? 1 : 0;
+      return AF_OK;
+    default:
+      return AF_EINVAL;
+  }
+}
+
+// The device error word is part of the workspace; reading it waits for the context's stream.
+extern "C" int af_last_device_error(af_ctx* ctx, int* flags, int clear) {
+  if (!ctx || !flags) return AF_ENULL;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  int* word = (int*)(ctx->ws + ctx->lay.tickets) + AF_TICKET_ERR;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return AF_EHIP;
+  if (hipMemcpy(flags, word, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return AF_EHIP;
+  if (clear && *flags) {
+    const int zero = 0;
+    if (hipMemcpy(word, &zero, sizeof(int), hipMemcpyHostToDevice) != hipSuccess) return AF_EHIP;
+  }
+  return AF_OK;
+}
+
 extern "C" int af_profile_set(af_ctx* ctx, void* dev_stamps, int n_slots) {
   if (!ctx) return AF_ENULL;
   if (dev_stamps != nullptr && n_slots <= 0) return AF_EINVAL;

@@ -22,260 +22,7 @@
 // split order, so the result does not depend on scheduling.
 #include "af_internal.h"
 #include "row_prologue.h"
-
-#define GEMV_LIST 2048  // rows given by the caller are staged this many at a time
-
-struct GemvParams {
-  const half_t* W;
-  af_row_src rows;
-  float* partials;
-  int* tickets;
-  void* y;
-  const half_t* residual;
-  int out, ld, y_kind, out_pad, use_lds_x;
-  int range_sel;  // threshold selection per channel range, no list for the whole vector
-  int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
-  // Output columns come in `slots` of cols_per_slot columns, each covered by tiles_per_slot
-  // tiles.  A plain GEMV has one slot.  With w_sel, slot s multiplies by the matrix
-  // W + w_sel[s] * w_stride (leading dimension ld), so the experts a router picked on the
-  // device are reached without a host round trip.  y_scale (device, one float) scales the
-  // product before the residual is added.
-  int cols_per_slot, tiles_per_slot;
-  const int* w_sel;
-  long long w_stride;
-  const float* y_scale;
-  // Router of a mixture-of-experts block run in this launch's front end (gate|up): every
-  // workgroup works out the experts itself from x and uses them for its slot; workgroup
-  // (0, 0) publishes them for the launches that follow.  Null router_Wr: no router.
-  const half_t* router_Wr;  // [router_E][in]
-  int router_E, router_top;
-  int32_t* router_experts;
-  float* router_weights;
-  float* router_logits;
-  long long* prof;  // time stamps of this launch (af_profile_set), or null
-};
-
-__device__ __forceinline__ void store_out(const GemvParams& p, int col, float v) {
-  if (p.y_scale) v *= *p.y_scale;
-  if (p.residual) v += (float)p.residual[col];
-  if (p.y_kind == AF_F16)
-    reinterpret_cast<half_t*>(p.y)[col] = (half_t)v;
-  else
-    reinterpret_cast<float*>(p.y)[col] = v;
-}
-
-// ROUTED: the instantiation that runs a mixture-of-experts router in its front end (kept apart
-// so that the plain launches do not carry its registers).
-template <int LX, int U, int NW, bool ROUTED>
-__global__ __launch_bounds__(NW * AF_WAVE) void gemv_f16_kernel(GemvParams p) {
-  constexpr int GEMV_THREADS = NW * AF_WAVE;
-  constexpr int GEMV_WAVES = NW;
-  constexpr int LY = AF_WAVE / LX;
-  constexpr int TW = LX * 8;
-  constexpr int STEP = GEMV_WAVES * LY;  // rows taken per workgroup iteration
-  constexpr int SCRATCH = RP_SCRATCH_WORDS > NW * TW ? RP_SCRATCH_WORDS : NW * TW;
-  typedef RowPrologue<GEMV_THREADS> RP;
-  extern __shared__ __align__(16) unsigned short xs[];  // the operator input, when built here
-  __shared__ __align__(16) unsigned s_scratch[SCRATCH];  // histograms, later the wave sums
-  __shared__ typename RP::Smem s_rp;
-  __shared__ int s_last;
-  float(*s_red)[TW] = reinterpret_cast<float(*)[TW]>(s_scratch);
-  // staged rows, (index << 16 | fp16 bits of x)
-  unsigned* s_list = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(xs) + p.list_off);
-
-  af_prof_begin(p.prof);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lx = lane % LX, ly = lane / LX;
-  const int slot = blockIdx.x / p.tiles_per_slot;
-  const int tile_in = blockIdx.x - slot * p.tiles_per_slot;   // tile inside the slot
-  const int col = tile_in * TW + lx * 8;                       // column inside the slot
-  // lanes past the slot's edge read the tile's first column and are dropped at the store
-  const int col_ld = col < p.cols_per_slot ? col : tile_in * TW;
-  const int S = gridDim.y, s = blockIdx.y;
-  const af_row_src& r = p.rows;
-
-  // Rows given and their number known on the host: fetch this thread's share of the first
-  // staging pass now, so that the index round trip overlaps the construction of x.
-  constexpr int PF = GEMV_LIST / GEMV_THREADS;
-  int pre[PF];
-  const bool prefetched = r.sel == AF_ROWS_GIVEN && r.idx != nullptr && r.nidx_dev == nullptr;
-  if (prefetched) {
-    const int R = (r.nidx_host + S - 1) / S;
-    const int r0 = min(s * R, r.nidx_host), r1 = min(r0 + R, r.nidx_host);
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      const int i = r0 + tid + u * GEMV_THREADS;
-      pre[u] = i < r1 ? r.idx[i] : 0;
-    }
-  }
-
-  constexpr int RE = 8;  // experts the in-kernel router handles
-  constexpr bool routed = ROUTED;
-  half8 wr[routed ? RE : 1];
-  if constexpr (routed) {  // this thread's router weights do not depend on x: fetch them before x is built
-#pragma unroll
-    for (int e = 0; e < RE; ++e) {
-#pragma unroll
-      for (int c = 0; c < 8; ++c) wr[e][c] = (half_t)0;
-      if (e < p.router_E && tid < (r.n >> 3))
-        wr[e] = *reinterpret_cast<const half8*>(p.router_Wr + (size_t)e * r.n + (size_t)tid * 8);
-    }
-  }
-  if (p.use_lds_x && (!p.range_sel || routed))
-    RP::produce(r, xs, s_rp, s == 0, blockIdx.x, gridDim.x,
-                r.sel == AF_SEL_TOPK ? s_scratch : nullptr);
-  if constexpr (routed) {
-    RP::template router_in_lds<RE>(xs, r.n, s_rp, wr, p.router_E, p.router_top);
-    if (blockIdx.x == 0 && s == 0) {
-      if (tid < p.router_top) {
-        p.router_experts[tid] = s_rp.experts[tid];
-        p.router_weights[tid] = s_rp.weights[tid];
-      }
-      if (tid < p.router_E) p.router_logits[tid] = s_rp.logit[tid];
-    }
-  }
-
-  float acc[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
-  const half_t* wcol = p.W + col_ld;
-  if (routed)
-    wcol += (size_t)s_rp.experts[slot] * (size_t)p.w_stride;
-  else if (p.w_sel)
-    wcol += (size_t)p.w_sel[slot] * (size_t)p.w_stride;
-
-  // One pass over `cnt` staged rows of s_list.
-  auto stream = [&](int cnt) {
-    int i = wave * LY + ly;
-    for (; i + (U - 1) * STEP < cnt; i += U * STEP) {
-      half8 w[U];
-      unsigned e[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        e[u] = s_list[i + u * STEP];
-        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e[u] & 0xFFFFu));
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv;
-      }
-    }
-    // Ragged end: one more batch of the same depth with the missing rows masked off, so its
-    // loads are all in flight together (a row-at-a-time loop would pay one memory round trip
-    // per row, up to U - 1 of them in a row).
-    if (i < cnt) {
-      half8 w[U];
-      unsigned e[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const bool ok = i + u * STEP < cnt;
-        e[u] = ok ? s_list[i + u * STEP] : 0u;
-        if (ok) {
-          w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
-        } else {
-#pragma unroll
-          for (int c = 0; c < 8; ++c) w[u][c] = (half_t)0;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float xv = (float)__builtin_bit_cast(half_t, (unsigned short)(e[u] & 0xFFFFu));
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] += (float)w[u][c] * xv;
-      }
-    }
-  };
-
-  if (p.range_sel) {
-    stream(routed ? RP::threshold_range_of_full(r, xs, s_rp, s_list, S, s)
-                  : RP::threshold_range(r, xs, s_rp, s_list, S, s, blockIdx.x == 0));
-  } else if (r.sel != AF_ROWS_GIVEN) {
-    int nidx_total;
-    const int cnt = RP::select_split(r, xs, s_scratch, s_rp, s_list, S, s, blockIdx.x == 0,
-                                     blockIdx.x == 0 && s == 0, &nidx_total, p.use_lds_x != 0);
-    stream(cnt);
-  } else {
-    int nidx = r.nidx_host;
-    if (r.nidx_dev) nidx = min(*r.nidx_dev, nidx);
-    const int R = (nidx + S - 1) / S;
-    const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
-    const unsigned short* xg = reinterpret_cast<const unsigned short*>(r.src);
-    for (int base = r0; base < r1; base += GEMV_LIST) {
-      const int cnt = min(GEMV_LIST, r1 - base);
-      __syncthreads();
-      if (prefetched && base == r0) {
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-          const int i = tid + u * GEMV_THREADS;
-          if (i < cnt) {
-            const int j = pre[u];
-            const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
-            s_list[i] = ((unsigned)j << 16) | bits;
-          }
-        }
-      } else {
-        for (int i = tid; i < cnt; i += GEMV_THREADS) {
-          const int j = r.idx ? r.idx[base + i] : base + i;
-          const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
-          s_list[i] = ((unsigned)j << 16) | bits;
-        }
-      }
-      __syncthreads();
-      stream(cnt);
-    }
-  }
-  __syncthreads();  // s_scratch changes its role: histograms -> wave sums
-
-  // lane groups -> one row of sums per wave
-#pragma unroll
-  for (int off = LX; off < AF_WAVE; off <<= 1)
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] += __shfl_xor(acc[c], off, AF_WAVE);
-  if (ly == 0) {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) s_red[wave][lx * 8 + c] = acc[c];
-  }
-  __syncthreads();
-
-  const int tile0 = blockIdx.x * TW;                      // in the padded column space
-  const int out0 = slot * p.cols_per_slot + tile_in * TW;  // first output column of the tile
-  const int valid = min(TW, p.cols_per_slot - tile_in * TW);
-  if (S == 1) {
-    for (int c = tid; c < valid; c += GEMV_THREADS) {
-      float v = 0.f;
-#pragma unroll
-      for (int w = 0; w < GEMV_WAVES; ++w) v += s_red[w][c];
-      store_out(p, out0 + c, v);
-    }
-    af_prof_end(p.prof);
-    return;
-  }
-
-  float* mine = p.partials + (size_t)s * p.out_pad;
-  for (int c = tid; c < TW; c += GEMV_THREADS) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < GEMV_WAVES; ++w) v += s_red[w][c];
-    af_store_agent(mine + tile0 + c, v);  // out_pad covers whole tiles
-  }
-  af_stores_done();
-  __syncthreads();
-  if (tid == 0) {
-    int old = af_ticket_take(&p.tickets[blockIdx.x]);
-    s_last = (old == S - 1);
-  }
-  __syncthreads();
-  if (!s_last) {
-    af_prof_end(p.prof);
-    return;
-  }
-  for (int c = tid; c < valid; c += GEMV_THREADS)
-    store_out(p, out0 + c, af_sum_partials(p.partials + tile0 + c, p.out_pad, S));
-  if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);  // ready for the next launch
-  af_prof_end(p.prof);
-}
+#include "gemv_f16_body.h"
 
 // Tile width, waves per workgroup and split count for a shape.  AF_GEMV_LX / AF_GEMV_NW /
 // AF_GEMV_SPLIT / AF_GEMV_WGS in the environment override the heuristic (tuning sweeps).
@@ -344,13 +91,16 @@ static void launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const GemvP
     launch_one<LX, 4, false>(grid, lds, st, p);
 }
 
-int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
+int af_plan_gemv_f16(af_ctx* ctx, const af_gemv_args& a, bool whole_layer, GemvPlan* plan) {
   const af_row_src& r = a.rows;
   // the largest index set this launch can meet (the count of a threshold set is only known
   // on the device)
   int max_rows = r.sel == AF_SEL_TOPK ? r.k : (r.sel == AF_SEL_THRESHOLD ? r.n : r.nidx_host);
   int lx, nw, S;
-  choose_config(ctx, a.out, max_rows, r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, &lx, &nw, &S);
+  // inside the whole-layer kernel every operator runs on the kernel's 1024-thread workgroups,
+  // one per compute unit
+  choose_config(ctx, a.out, max_rows,
+                whole_layer || r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, &lx, &nw, &S);
   const int tw = lx * 8;
   // output slots (one per device-selected matrix; a single one otherwise), whole tiles each
   const int n_slots = a.w_sel ? a.n_slots : 1;
@@ -375,7 +125,8 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
                         a.router_Wr != nullptr))
     return AF_EWORKSPACE;
   if (S > 1 && (size_t)S * out_pad > ctx->lay.partial_floats) return AF_EWORKSPACE;
-  GemvParams p;
+  GemvParams& p = plan->p;
+  p = GemvParams{};
   p.W = (const half_t*)a.W;
   p.rows = r;
   p.partials = (float*)(ctx->ws + ctx->lay.partials);
@@ -384,10 +135,9 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.residual = a.residual;
   p.out = a.out;
   p.ld = a.ld;
-  p.y_kind = a.y_kind;
   p.out_pad = out_pad;
-  p.use_lds_x = use_lds_x ? 1 : 0;
-  p.range_sel = range_sel ? 1 : 0;
+  p.flags = (a.y_kind == AF_F32 ? GEMV_F_F32 : 0) | (use_lds_x ? GEMV_F_LDS_X : 0) |
+            (range_sel ? GEMV_F_RANGE_SEL : 0);
   p.list_off = (int)xs_bytes;
   p.cols_per_slot = cols_per_slot;
   p.tiles_per_slot = tiles_per_slot;
@@ -400,15 +150,26 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
   p.router_experts = a.router_experts;
   p.router_weights = a.router_weights;
   p.router_logits = a.router_logits;
-  p.prof = af_prof_take(ctx);
-  const size_t lds = xs_bytes + (size_t)list_cap * 4;
-  dim3 grid(tiles, S);
-  if (lx == 64)
-    launch_lx<64>(nw, grid, lds, ctx->stream, p);
-  else if (lx == 32)
-    launch_lx<32>(nw, grid, lds, ctx->stream, p);
+  plan->tiles = tiles;
+  plan->S = S;
+  plan->lx = lx;
+  plan->nw = nw;
+  plan->lds = xs_bytes + (size_t)list_cap * 4;
+  return AF_OK;
+}
+
+int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a) {
+  GemvPlan plan;
+  const int rc = af_plan_gemv_f16(ctx, a, false, &plan);
+  if (rc) return rc;
+  plan.p.prof = af_prof_take(ctx);
+  dim3 grid(plan.tiles, plan.S);
+  if (plan.lx == 64)
+    launch_lx<64>(plan.nw, grid, plan.lds, ctx->stream, plan.p);
+  else if (plan.lx == 32)
+    launch_lx<32>(plan.nw, grid, plan.lds, ctx->stream, plan.p);
   else
-    launch_lx<16>(nw, grid, lds, ctx->stream, p);
+    launch_lx<16>(plan.nw, grid, plan.lds, ctx->stream, plan.p);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }

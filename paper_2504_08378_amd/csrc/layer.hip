@@ -17,6 +17,7 @@
 
 #include "af_internal.h"
 #include "row_prologue.h"
+#include "gemv_f16_body.h"
 
 #define ATT_THREADS 256
 #define ATT_WAVES (ATT_THREADS / AF_WAVE)
@@ -29,7 +30,7 @@ struct AttnParams {
   half_t* out;         // [n_heads*HD]
   float* part;         // [n_heads][KS][HD+2]
   int* tickets;        // [n_heads]
-  int n_heads, n_kv, kv_len, kv_cap;
+  int n_heads, n_kv, kv_len, kv_cap, head_dim;
   long long* prof;     // time stamps of this launch (af_profile_set), or null
   float cs[64], sn[64];  // cos / sin of pos * theta^(-2i/HD), i < HD/2, formed in fp64 on the host
 };
@@ -275,6 +276,7 @@ static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* 
   p.n_kv = cfg->n_kv_heads;
   p.kv_len = kv_len;
   p.kv_cap = kv_cap;
+  p.head_dim = cfg->head_dim;
   p.prof = af_prof_take(ctx);
   for (int i = 0; i < cfg->head_dim / 2; ++i) {
     const double ang = (double)pos * pow((double)cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
@@ -290,13 +292,364 @@ static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* 
   return AF_OK;
 }
 
+// ---- whole-layer kernel -------------------------------------------------------------------
+// The five operators of a layer as phases of ONE launch of 1024-thread workgroups, one per
+// compute unit, all resident at once.  A phase hands its result to the next one through
+// memory: the workgroup that completes a tile (or a head) stores it through to memory, waits
+// for the acknowledgement and adds one to the phase's counter; a workgroup enters a phase once
+// the counter of the phase before has reached its total.  Every address a phase reads with
+// plain loads is written at most once per launch and only before that phase starts, so no
+// compute unit can hold a stale copy.  Waits are bounded: a wait that does not end sets the
+// device error word and the workgroup leaves the kernel, so the grid always drains.
+// What the phases do not depend on is fetched before the wait (the attention phase loads its
+// share of the KV cache while the qkv projection is still being reduced).
+#define LAYER_THREADS 1024
+#define LAYER_WAVES (LAYER_THREADS / AF_WAVE)
+#define LAYER_SPIN_LIMIT (1 << 21)
+#define LAYER_ATT_MAX_KEYS 2048
+
+struct LayerParams {
+  GemvParams g[4];  // qkv, o, gate|up, down
+  int tiles[4], S[4], lx[4];
+  AttnParams at;
+  int KS;           // key splits per head
+  int* done;        // [5] phase counters: qkv, attention, o, gate|up, down
+  int* err;
+};
+
+// All threads of the workgroup wait until *counter >= target (polled by one thread); false if
+// the bounded wait ran out (the error word is set, the caller leaves the kernel).
+__device__ __forceinline__ bool layer_wait(const int* counter, int target, int* err, int& s_flag) {
+  if (threadIdx.x == 0) {
+    int ok = 0;
+    for (int i = 0; i < LAYER_SPIN_LIMIT; ++i) {
+      if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+        ok = 1;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(2);
+    }
+    if (!ok) __hip_atomic_fetch_or(err, (int)AF_DEVERR_SPIN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_flag = ok;
+  }
+  __syncthreads();
+  const bool ok = s_flag != 0;
+  __syncthreads();  // s_flag may be rewritten by the next wait
+  return ok;
+}
+
+// LDS of the attention phase, carved from the dynamic region (floats).
+template <int HD>
+struct AttnLds {
+  static constexpr int LPK = HD / 8;
+  static constexpr int KPB = LAYER_THREADS / LPK;
+  static constexpr int PARTS = LAYER_THREADS / HD;
+  static constexpr int Q = 0, KNEW = HD, VNEW = 2 * HD, RED = 3 * HD, SC = 3 * HD + 32,
+                       PV = SC + LAYER_ATT_MAX_KEYS + 16, PV2 = PV + KPB * HD, END = PV2 + PARTS * HD;
+};
+#define LAYER_ATT_LDS_BYTES (4 * (AttnLds<128>::END > AttnLds<64>::END ? AttnLds<128>::END : AttnLds<64>::END))
+
+// Attention of (head h, key split s) by one 1024-thread workgroup; same arithmetic as
+// attn_decode_kernel.  The cached keys and values of the split are requested first, then the
+// workgroup waits for the qkv projection (counter `ready` reaching `ready_total`).
+template <int HD>
+__device__ __forceinline__ bool attn_phase(const AttnParams& p, int h, int s, int KS, float* lds,
+                                           int& s_last, int& s_flag, const int* ready, int ready_total,
+                                           int* done, int* done_prev, int* err) {
+  typedef AttnLds<HD> L;
+  constexpr int LPK = L::LPK, KPB = L::KPB, NB = 2, PARTS = L::PARTS;
+  float* s_q = lds + L::Q;
+  float* s_knew = lds + L::KNEW;
+  float* s_vnew = lds + L::VNEW;
+  float* s_red = lds + L::RED;
+  float* s_sc = lds + L::SC;
+  float(*s_pv)[HD] = reinterpret_cast<float(*)[HD]>(lds + L::PV);
+  float(*s_pv2)[HD] = reinterpret_cast<float(*)[HD]>(lds + L::PV2);
+  unsigned short* s_out = reinterpret_cast<unsigned short*>(lds + L::KNEW);  // reused for the result
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rep = p.n_heads / p.n_kv, kvh = h / rep;
+  const int T = p.kv_len;
+  const int KP = (T + KS - 1) / KS;
+  const int t0 = min(s * KP, T), t1 = min(t0 + KP, T);
+  const int cnt = t1 - t0;
+  const bool owns_new = (s == KS - 1);
+  const int total = cnt + (owns_new ? 1 : 0);
+
+  const half_t* q = p.qkv + (size_t)h * HD;
+  const half_t* kn = p.qkv + (size_t)(p.n_heads + kvh) * HD;
+  const half_t* vn = p.qkv + (size_t)(p.n_heads + p.n_kv + kvh) * HD;
+  half_t* Kc = p.k_cache + (size_t)kvh * p.kv_cap * HD;
+  half_t* Vc = p.v_cache + (size_t)kvh * p.kv_cap * HD;
+  const int lk = tid % LPK, kq = tid / LPK;  // my slice of the head dim, my key slot
+  half8 zero8;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) zero8[c] = (half_t)0;
+
+  // cached rows first: they do not depend on this token
+  half8 kv[NB], vv[NB];
+#pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    const int i = kq + u * KPB;
+    const bool ok = i < cnt;
+    kv[u] = ok ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    vv[u] = ok ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+  }
+  if (!layer_wait(ready, ready_total, err, s_flag)) return false;
+  af_prof_begin(p.prof);
+
+  if (tid < HD / 2) {
+    const float a = (float)q[tid], b = (float)q[tid + HD / 2];
+    const float cs = p.cs[tid], sn = p.sn[tid];
+    const float sc = 1.0f / sqrtf((float)HD);
+    s_q[tid] = (a * cs - b * sn) * sc;
+    s_q[tid + HD / 2] = (b * cs + a * sn) * sc;
+  } else if (owns_new && tid >= 64 && tid < 64 + HD / 2) {
+    const int i = tid - 64;
+    const float a = (float)kn[i], b = (float)kn[i + HD / 2];
+    const float cs = p.cs[i], sn = p.sn[i];
+    const half_t ha = (half_t)(a * cs - b * sn), hb = (half_t)(b * cs + a * sn);  // cache is fp16
+    s_knew[i] = (float)ha;
+    s_knew[i + HD / 2] = (float)hb;
+    if (h % rep == 0) {
+      Kc[(size_t)p.kv_len * HD + i] = ha;
+      Kc[(size_t)p.kv_len * HD + i + HD / 2] = hb;
+    }
+  } else if (owns_new && tid >= 128 && tid < 128 + HD) {
+    const int i = tid - 128;
+    const half_t v = vn[i];
+    s_vnew[i] = (float)v;
+    if (h % rep == 0) Vc[(size_t)p.kv_len * HD + i] = v;
+  }
+  __syncthreads();
+
+  // ---- scores ------------------------------------------------------------------------
+  float qr[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) qr[c] = s_q[lk * 8 + c];
+  auto score = [&](const half8& k8, int i) {
+    float d = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) d += (float)k8[c] * qr[c];
+#pragma unroll
+    for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off, AF_WAVE);
+    if (lk == 0 && i < cnt) s_sc[i] = d;
+  };
+#pragma unroll
+  for (int u = 0; u < NB; ++u) score(kv[u], kq + u * KPB);
+  for (int i0 = kq + NB * KPB; i0 < cnt; i0 += NB * KPB) {  // long caches: further batches
+    half8 k2[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      k2[u] = i < cnt ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) score(k2[u], i0 + u * KPB);
+  }
+  if (owns_new && wave == 0) {
+    float d = 0.f;
+    for (int c = lane; c < HD; c += AF_WAVE) d += s_q[c] * s_knew[c];
+    d = af_wave_sum(d);
+    if (lane == 0) s_sc[cnt] = d;
+  }
+  __syncthreads();
+
+  // ---- local softmax -----------------------------------------------------------------
+  float m = -INFINITY;
+  for (int i = tid; i < total; i += LAYER_THREADS) m = fmaxf(m, s_sc[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, AF_WAVE));
+  if (lane == 0) s_red[wave] = m;
+  __syncthreads();
+  m = s_red[0];
+#pragma unroll
+  for (int w = 1; w < LAYER_WAVES; ++w) m = fmaxf(m, s_red[w]);
+  __syncthreads();
+  float l = 0.f;
+  for (int i = tid; i < total; i += LAYER_THREADS) {
+    float e = expf(s_sc[i] - m);
+    s_sc[i] = e;
+    l += e;
+  }
+  l = af_wave_sum(l);
+  if (lane == 0) s_red[wave] = l;
+  __syncthreads();
+  l = 0.f;
+#pragma unroll
+  for (int w = 0; w < LAYER_WAVES; ++w) l += s_red[w];
+
+  // ---- weighted values ---------------------------------------------------------------
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+#pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    const int i = kq + u * KPB;
+    const float pw = i < cnt ? s_sc[i] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] += pw * (float)vv[u][c];
+  }
+  for (int i0 = kq + NB * KPB; i0 < cnt; i0 += NB * KPB) {
+    half8 v2[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      v2[u] = i < cnt ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int i = i0 + u * KPB;
+      const float pw = i < cnt ? s_sc[i] : 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] += pw * (float)v2[u][c];
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s_pv[kq][lk * 8 + c] = acc[c];
+  __syncthreads();
+  {  // key slots -> PARTS partial rows -> one row, always in slot order
+    const int c = tid % HD, part = tid / HD;
+    constexpr int PER = KPB / PARTS;
+    float v = 0.f;
+#pragma unroll 4
+    for (int g = 0; g < PER; ++g) v += s_pv[part * PER + g][c];
+    s_pv2[part][c] = v;
+  }
+  __syncthreads();
+  float* mine = p.part + ((size_t)h * KS + s) * (HD + 2);
+  unsigned short* outp = reinterpret_cast<unsigned short*>(p.out) + (size_t)h * HD;
+  if (tid < HD) {
+    float v = 0.f;
+#pragma unroll
+    for (int g = 0; g < PARTS; ++g) v += s_pv2[g][tid];
+    if (owns_new) v += s_sc[cnt] * s_vnew[tid];
+    if (KS == 1) {
+      s_out[tid] = __builtin_bit_cast(unsigned short, (half_t)(v / l));
+    } else {
+      af_store_agent(mine + 2 + tid, v);
+    }
+  }
+  bool finisher = KS == 1;
+  if (KS > 1) {
+    if (tid == 0) {
+      af_store_agent(mine, m);
+      af_store_agent(mine + 1, l);
+    }
+    af_stores_done();
+    __syncthreads();
+    if (tid == 0) {
+      int old = af_ticket_take(&p.tickets[h]);
+      s_last = (old == KS - 1);
+    }
+    __syncthreads();
+    finisher = s_last != 0;
+    if (finisher) {
+      // combine the splits in split order; loads go out eight splits at a time
+      const float* base = p.part + (size_t)h * KS * (HD + 2);
+      if (tid < HD) {
+        float M = -INFINITY;
+        for (int q0 = 0; q0 < KS; q0 += 8) {
+          float ms[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            ms[u] = q0 + u < KS ? af_load_agent(base + (size_t)(q0 + u) * (HD + 2)) : -INFINITY;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) M = fmaxf(M, ms[u]);
+        }
+        float Lsum = 0.f, v = 0.f;
+        for (int q0 = 0; q0 < KS; q0 += 8) {
+          float ms[8], ls[8], av[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const bool ok = q0 + u < KS;
+            const float* pp = base + (size_t)(q0 + u) * (HD + 2);
+            ms[u] = ok ? af_load_agent(pp) : -INFINITY;
+            ls[u] = ok ? af_load_agent(pp + 1) : 0.f;
+            av[u] = ok ? af_load_agent(pp + 2 + tid) : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (ms[u] != -INFINITY) {  // an empty split has nothing to add
+              const float wgt = expf(ms[u] - M);
+              Lsum += wgt * ls[u];
+              v += wgt * av[u];
+            }
+          }
+        }
+        s_out[tid] = __builtin_bit_cast(unsigned short, (half_t)(v / Lsum));
+      }
+      if (tid == 0) af_ticket_reset(&p.tickets[h]);
+    }
+  }
+  if (finisher) {  // one finished head: stored through as 8-byte pieces, acknowledged, then counted
+    __syncthreads();
+    if (tid < HD / 4)
+      __hip_atomic_store(reinterpret_cast<unsigned long long*>(outp) + tid,
+                         reinterpret_cast<const unsigned long long*>(s_out)[tid], __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    af_stores_done();
+    __syncthreads();
+    if (tid == 0) {
+      const int old = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == p.n_heads - 1)
+        __hip_atomic_store(done_prev, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  af_prof_end(p.prof);
+  return true;
+}
+
+// One GEMV phase: operator OP of the layer (0 qkv, 1 o, 2 gate|up, 3 down) in phase PH.
+template <int LX, int OP, int PH>
+__device__ __forceinline__ bool layer_gemv_phase(const LayerParams& P, int w, unsigned short* xs,
+                                                 GemvLds<LAYER_WAVES>& lds, int& s_flag) {
+  const int tiles = P.tiles[OP], S = P.S[OP];
+  if (w >= tiles * S) return true;
+  if (PH > 0) {
+    const int need = PH == 2 ? P.at.n_heads : P.tiles[OP - 1];
+    if (!layer_wait(P.done + PH - 1, need, P.err, s_flag)) return false;
+  }
+  const GemvPos vb = {w % tiles, w / tiles, tiles, S};
+  const GemvParams g = P.g[OP];  // a copy of its own: the fields settle in scalar registers
+  gemv_f16_body<LX, 8, LAYER_WAVES, false, true>(g, vb, xs, lds);
+  __syncthreads();  // the next phase reuses the workgroup's LDS
+  return true;
+}
+
+// LX_GU: lanes across a tile of the gate|up operator (its rows are the longest); the other
+// operators use 16 (128-column tiles).
+template <int LX_GU>
+__global__ __launch_bounds__(LAYER_THREADS) void layer_f16_kernel(LayerParams P) {
+  extern __shared__ __align__(16) unsigned short xs[];
+  __shared__ GemvLds<LAYER_WAVES> lds;
+  __shared__ int s_flag;
+  const int w = blockIdx.x;
+  if (!layer_gemv_phase<16, 0, 0>(P, w, xs, lds, s_flag)) return;
+  if (w < P.at.n_heads * P.KS) {
+    const int h = w % P.at.n_heads, s = w / P.at.n_heads;
+    bool ok;
+    if (P.at.head_dim == 128)
+      ok = attn_phase<128>(P.at, h, s, P.KS, reinterpret_cast<float*>(xs), lds.last, s_flag, P.done + 0,
+                           P.tiles[0], P.done + 1, P.done + 0, P.err);
+    else
+      ok = attn_phase<64>(P.at, h, s, P.KS, reinterpret_cast<float*>(xs), lds.last, s_flag, P.done + 0,
+                          P.tiles[0], P.done + 1, P.done + 0, P.err);
+    if (!ok) return;
+    __syncthreads();
+  }
+  if (!layer_gemv_phase<16, 1, 2>(P, w, xs, lds, s_flag)) return;
+  if (!layer_gemv_phase<LX_GU, 2, 3>(P, w, xs, lds, s_flag)) return;
+  layer_gemv_phase<16, 3, 4>(P, w, xs, lds, s_flag);
+}
+
 static int check_layer_args(const af_ctx* ctx, const af_layer_cfg* cfg, const af_select_cfg* sel,
                             int kv_len, int kv_cap, int pos) {
   if (cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->d_ffn <= 0)
     return AF_EINVAL;
   if (cfg->head_dim != 128 && cfg->head_dim != 64) return AF_ESHAPE;
   if (cfg->n_heads % cfg->n_kv_heads) return AF_ESHAPE;
-  if (cfg->n_heads > AF_N_TICKETS - AF_TICKET_ATTN) return AF_ESHAPE;
+  if (cfg->n_heads > AF_TICKET_PHASE - AF_TICKET_ATTN) return AF_ESHAPE;
   if (cfg->d_model % 8 || cfg->d_ffn % 8) return AF_ESHAPE;
   if (cfg->weight_kind != AF_W_F16 && cfg->weight_kind != AF_W_Q4G32 &&
       cfg->weight_kind != AF_W_Q4CL)
@@ -323,6 +676,99 @@ static int check_layer_args(const af_ctx* ctx, const af_layer_cfg* cfg, const af
   int max_i = cfg->d_ffn > qdim ? cfg->d_ffn : qdim;
   if (cfg->d_model > max_i) max_i = cfg->d_model;
   if (max_w > ctx->max_out || max_i > ctx->max_in) return AF_EWORKSPACE;
+  return AF_OK;
+}
+
+// The layer as one launch (fp16 weights).  Returns 1 if the configuration does not fit the
+// whole-layer kernel (the caller then launches the operators one by one), else a status.
+static int launch_layer_kernel(af_ctx* ctx, const af_layer_cfg* cfg, const af_gemv_args* ga,
+                               const half_t* qkv, void* kc, void* vc, int kv_len, int kv_cap, int pos,
+                               half_t* attn) {
+  if (!ctx->use_layer_kernel || ctx->layer_kernel_state < 0) return 1;
+  if (ctx->layer_kernel_state == 0) {
+    // every workgroup of the grid has to be resident at the same time: one per compute unit
+    int per_cu = 0;
+    bool ok = true;
+    const void* fns[2] = {reinterpret_cast<const void*>(layer_f16_kernel<16>),
+                          reinterpret_cast<const void*>(layer_f16_kernel<64>)};
+    for (const void* fn : fns) {
+      per_cu = 0;
+      if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET) != hipSuccess ||
+          hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, LAYER_THREADS, AF_GEMV_LDS_BUDGET) != hipSuccess ||
+          per_cu < 1)
+        ok = false;
+    }
+    if (!ok) {
+      (void)hipGetLastError();
+      ctx->layer_kernel_state = -1;
+      return 1;
+    }
+    ctx->layer_kernel_state = 1;
+  }
+  if (cfg->n_heads > ctx->n_cu) return 1;
+  for (int op = 0; op < 4; ++op)
+    if ((uintptr_t)ga[op].y & 7u) return 1;  // results leave as 8-byte stores
+  LayerParams P{};
+  size_t lds = LAYER_ATT_LDS_BYTES;
+  int n_wg = 0;
+  for (int op = 0; op < 4; ++op) {
+    if (ga[op].w_sel || ga[op].y_scale || ga[op].router_Wr) return 1;
+    GemvPlan plan;
+    if (af_plan_gemv_f16(ctx, ga[op], true, &plan) != AF_OK) return 1;  // the per-operator path reports it
+    if (plan.nw != LAYER_WAVES || plan.tiles * plan.S > ctx->n_cu) return 1;
+    P.g[op] = plan.p;
+    P.tiles[op] = plan.tiles;
+    P.S[op] = plan.S;
+    P.lx[op] = plan.lx;
+    if (plan.lx != 16 && !(op == 2 && plan.lx == 64)) return 1;  // the tile shapes the kernel is built for
+    if (plan.lds > lds) lds = plan.lds;
+    if (plan.tiles * plan.S > n_wg) n_wg = plan.tiles * plan.S;
+  }
+  if (lds > AF_GEMV_LDS_BUDGET) return 1;
+  int KS = (kv_len + 63) / 64;
+  if (KS < 1) KS = 1;
+  if (KS > 64) KS = 64;
+  if (KS > ctx->n_cu / cfg->n_heads) KS = ctx->n_cu / cfg->n_heads;
+  while ((size_t)cfg->n_heads * KS * (cfg->head_dim + 2) > ctx->lay.attn_floats && KS > 1) --KS;
+  if ((kv_len + KS - 1) / KS > LAYER_ATT_MAX_KEYS) return 1;
+  if (cfg->n_heads * KS > n_wg) n_wg = cfg->n_heads * KS;
+  int* counters = (int*)(ctx->ws + ctx->lay.tickets);
+  P.done = counters + AF_TICKET_PHASE;
+  P.err = counters + AF_TICKET_ERR;
+  P.KS = KS;
+  AttnParams& a = P.at;
+  a.qkv = qkv;
+  a.k_cache = (half_t*)kc;
+  a.v_cache = (half_t*)vc;
+  a.out = attn;
+  a.part = (float*)(ctx->ws + ctx->lay.attn_part);
+  a.tickets = counters + AF_TICKET_ATTN;
+  a.n_heads = cfg->n_heads;
+  a.n_kv = cfg->n_kv_heads;
+  a.kv_len = kv_len;
+  a.kv_cap = kv_cap;
+  a.head_dim = cfg->head_dim;
+  for (int i = 0; i < cfg->head_dim / 2; ++i) {
+    const double ang = (double)pos * pow((double)cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
+    a.cs[i] = (float)cos(ang);
+    a.sn[i] = (float)sin(ang);
+  }
+  // phase counters: qkv 0, attention 1, o 2, gate|up 3, down 4 (time stamps in the same order)
+  const int phase_of[4] = {0, 2, 3, 4};
+  for (int op = 0; op < 4; ++op) {
+    const int ph = phase_of[op];
+    P.g[op].done = P.done + ph;
+    P.g[op].done_total = P.tiles[op];
+    P.g[op].flags |= (ph > 0 ? GEMV_F_DONE_PREV : 0) | (ph == 4 ? GEMV_F_DONE_LAST : 0);
+  }
+  P.g[0].prof = af_prof_take(ctx);
+  a.prof = af_prof_take(ctx);
+  for (int op = 1; op < 4; ++op) P.g[op].prof = af_prof_take(ctx);
+  if (P.lx[2] == 64)
+    hipLaunchKernelGGL(layer_f16_kernel<64>, dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+  else
+    hipLaunchKernelGGL(layer_f16_kernel<16>, dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+  AF_LAUNCH_CHECK();
   return AF_OK;
 }
 
@@ -362,9 +808,9 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
 
   // GEMV at selection point p.  fused: the kernel builds x from `src_v` (producer) and selects
   // for itself; otherwise x is ready in `x` and the rows come from pt[p].
-  auto gemv = [&](int p, const void* W, const void* Sc, int in, int out, int producer,
+  auto make = [&](int p, const void* W, const void* Sc, int in, int out, int producer,
                   const half_t* src_v, const half_t* gain, half_t* x, half_t* y,
-                  const half_t* res) -> int {
+                  const half_t* res) -> af_gemv_args {
     af_gemv_args a{};
     a.W = W;
     a.scales = (const half_t*)Sc;
@@ -398,20 +844,23 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
       r.nidx_host = pt[p].nidx_host;
       r.nidx_dev = pt[p].nidx_dev;
     }
-    return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a);
+    return a;
   };
-
-  if ((rc = gemv(0, w->Wqkv, w->Sqkv, d, qkv_out, AF_PRO_RMSNORM, h_in,
-                 (const half_t*)w->g_attn_norm, x0, qkv, nullptr)))
-    return rc;
+  const af_gemv_args ga[4] = {
+      make(0, w->Wqkv, w->Sqkv, d, qkv_out, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0, qkv, nullptr),
+      make(1, w->Wo, w->So, qdim, d, AF_PRO_NONE, attn, nullptr, nullptr, hmid, h_in),
+      make(2, w->Wgateup, w->Sgateup, d, 2 * f, AF_PRO_RMSNORM, hmid, (const half_t*)w->g_ffn_norm, x2, gu, nullptr),
+      make(3, w->Wdown, w->Sdown, f, d, AF_PRO_SILUMUL, gu, nullptr, x3, h_out, hmid)};
+  if (!q4) {
+    rc = launch_layer_kernel(ctx, cfg, ga, qkv, kc, vc, kv_len, kv_cap, pos, attn);
+    if (rc != 1) return rc;
+  }
+  auto gemv = [&](const af_gemv_args& a) { return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a); };
+  if ((rc = gemv(ga[0]))) return rc;
   if ((rc = launch_attention(ctx, cfg, qkv, kc, vc, kv_len, kv_cap, pos, attn))) return rc;
-  if ((rc = gemv(1, w->Wo, w->So, qdim, d, AF_PRO_NONE, attn, nullptr, nullptr, hmid, h_in)))
-    return rc;
-  if ((rc = gemv(2, w->Wgateup, w->Sgateup, d, 2 * f, AF_PRO_RMSNORM, hmid,
-                 (const half_t*)w->g_ffn_norm, x2, gu, nullptr)))
-    return rc;
-  if ((rc = gemv(3, w->Wdown, w->Sdown, f, d, AF_PRO_SILUMUL, gu, nullptr, x3, h_out, hmid)))
-    return rc;
+  if ((rc = gemv(ga[1]))) return rc;
+  if ((rc = gemv(ga[2]))) return rc;
+  if ((rc = gemv(ga[3]))) return rc;
   return AF_OK;
 }
 

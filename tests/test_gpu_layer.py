@@ -14,11 +14,24 @@ import synth_inputs as S
 from oracle import activeflow_oracle as O
 from paper_2504_08378_amd import binding as B
 from paper_2504_08378_amd import model as M
-from gpu_util import ctx, to_dev, to_host  # noqa: F401
+from gpu_util import to_dev, to_host  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
 KV_LEN, KV_CAP = 37, 48
+
+
+@pytest.fixture(scope="module", params=["launch_per_operator", "launch_per_layer"])
+def ctx(request):
+    """Every test of this file runs twice: with one launch per operator (the default) and with
+    the single launch per layer (AF_OPT_LAYER_KERNEL), which must give the same results.  The
+    device error word must stay clear (no bounded wait of the layer kernel may run out)."""
+    c = B.Context(0)
+    if request.param == "launch_per_layer":
+        c.set_option(B.AF_OPT_LAYER_KERNEL, 1)
+    yield c
+    assert c.last_device_error() == 0
+    c.close()
 
 
 def _ocfg(shape):
