@@ -69,7 +69,26 @@ const char* af_strerror(int status);
  * default.  It needs the GPU to itself for its duration (another kernel that occupies compute
  * units only delays it); configurations it does not cover (4-bit weights, more heads than
  * compute units, very long caches) take the per-operator path by themselves. */
-enum { AF_OPT_LAYER_KERNEL = 1 };
+/* AF_OPT_VALIDATE (default 0): with 1, every entry point that takes an index list from the caller
+ * (af_sparse_gemv_f16 / _q4 / _q4_cl, af_sparse_gemv_union_f16) first queues a check of the
+ * list's precondition (entries ascending, unique, inside [0, in)) on the stream; a violation
+ * sets AF_DEVERR_IDX in the device error word (af_last_device_error).  Independently of this
+ * option no kernel ever follows an index outside [0, in): such an entry contributes nothing to
+ * the result and sets the same bit.  A list that is in range but unsorted or repeated is only
+ * detected in validate mode; the GEMV then adds a repeated row twice.
+ * AF_OPT_TUNE_*: launch-shape overrides for tuning sweeps, 0 = the built-in choice: lanes across
+ * a tile (16, 32, 64), waves per workgroup (4, 8, 16), splits of the row list, workgroups
+ * aimed at.  AF_OPT_MOE_ROUTER_KERNEL: 1 runs the router of af_decode_moe_layer as a launch of
+ * its own instead of inside the gate|up launch. */
+enum {
+  AF_OPT_LAYER_KERNEL = 1,
+  AF_OPT_VALIDATE = 2,
+  AF_OPT_TUNE_LX = 3,
+  AF_OPT_TUNE_WAVES = 4,
+  AF_OPT_TUNE_SPLIT = 5,
+  AF_OPT_TUNE_WORKGROUPS = 6,
+  AF_OPT_MOE_ROUTER_KERNEL = 7
+};
 int af_set_option(af_ctx* ctx, int option, int value);
 
 /* Device error word of the context's workspace (host call; waits for the context's stream):
@@ -124,12 +143,20 @@ int af_pack_q4_g32(af_ctx* ctx, const void* W_f16, int out, int in, void* packed
                    void* scales_f16, int ld, int col0);
 int af_pack_q4_cl(af_ctx* ctx, const void* W_f16, int out, int in, void* packed,
                   void* scales_f16, int ld, int col0);
+/* af_unpack_q4_g32 (for tests): the inverse of af_pack_q4_g32 on the device, which pins the
+ * nibble order and the scale indexing the GEMV kernel relies on.  Reads the `out` columns at
+ * col0 of packed / scales (layout as above) and writes, in the out-major arrangement of the
+ * original matrix, q_i8 [out][in] = nibble - 8 (int8) and / or w_f32 [out][in] = (nibble - 8) *
+ * scale of the entry's group, exact in fp32.  Either output may be NULL. */
+int af_unpack_q4_g32(af_ctx* ctx, const void* packed, const void* scales_f16, int out, int in,
+                     int ld, int col0, void* q_i8, void* w_f32);
 
 /* ---- sparse GEMV: Section 4, operation C -----------------------------------------------
  * y[o] = sum over t < nidx of Wt[idx[t]][o] * x[idx[t]]  (+ residual[o] if given),
  * fp32 accumulation, o in [0, out).  Only the rows named by idx are read.
  *   idx == NULL means all channels 0..in-1 (dense).  Otherwise idx holds nidx entries
- *   (ascending, unique, in [0, in) -- a precondition, not checked); nidx is *nidx_dev if
+ *   (ascending, unique, in [0, in) -- a precondition; see AF_OPT_VALIDATE for what happens to
+ *   a list that breaks it); nidx is *nidx_dev if
  *   nidx_dev != NULL (a device int32 written by af_select_threshold, must be <= nidx_host)
  *   else nidx_host.  nidx == 0 gives y = residual (or 0).
  *   y: fp16 or fp32 [out] by y_kind; residual: fp16 [out] or NULL; y may alias residual.
@@ -198,8 +225,10 @@ int af_select_gemv_experts_f16(af_ctx* ctx, const void* Wt_all, const int32_t* e
  * Each of the B <= AF_MAX_BATCH tokens has its own index set idx_b[b][0..k); the kernel
  * reads every row of the union once and applies each token's mask:
  *   Y[b][o] = sum over j in idx_b[b] of Wt[j][o] * X[b][j].
- * X fp16 [B][in]; idx_b int32 [B][k]; union_idx int32 [in] and union_n int32 [1] receive
- * the ascending union and its size; Y [B][out] fp16 or fp32. */
+ * X fp16 [B][in]; idx_b int32 [B][k], every row ascending, unique, inside [0, in) (precondition
+ * as for af_sparse_gemv_f16; an entry out of range is dropped and reported, see
+ * AF_OPT_VALIDATE); union_idx int32 [in] and union_n int32 [1] receive the ascending union and
+ * its size; Y [B][out] fp16 or fp32. */
 int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
                              const void* X_f16, int B, const int32_t* idx_b, int k,
                              int32_t* union_idx, int32_t* union_n, void* Y, int y_kind);
@@ -423,7 +452,8 @@ int af_profile_set(af_ctx* ctx, void* dev_stamps, int n_slots);
 int af_wall_clock_khz(af_ctx* ctx); /* tick rate of those stamps; 0 if unknown */
 
 /* Stream capture helpers: record the calls made between begin and end into a HIP graph
- * and replay it.  The graph holds the pointers and scalars of the recorded calls. */
+ * and replay it.  The graph holds the pointers and scalars of the recorded calls: a captured
+ * decode call is valid for the one (pos, kv_len) and the buffers it was recorded with. */
 typedef struct af_graph af_graph;
 int af_capture_begin(af_ctx* ctx);
 int af_capture_end(af_ctx* ctx, af_graph** out);

@@ -23,7 +23,8 @@ AF_PRO_NONE, AF_PRO_RMSNORM, AF_PRO_SILUMUL = 0, 1, 2
 AF_MAX_N, AF_MAX_BATCH = 32768, 8
 AF_CALIB_BINS = 32768
 AF_NOALLOC_MAX_OUT, AF_ENOALLOC_LIMIT = 65536, -6
-AF_OPT_LAYER_KERNEL = 1
+AF_OPT_LAYER_KERNEL, AF_OPT_VALIDATE, AF_OPT_TUNE_LX, AF_OPT_TUNE_WAVES = 1, 2, 3, 4
+AF_OPT_TUNE_SPLIT, AF_OPT_TUNE_WORKGROUPS, AF_OPT_MOE_ROUTER_KERNEL = 5, 6, 7
 AF_DEVERR_SPIN, AF_DEVERR_IDX = 1, 2
 
 EXPORTS = [
@@ -37,6 +38,7 @@ EXPORTS = [
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
     "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
     "af_profile_set", "af_wall_clock_khz", "af_set_option", "af_last_device_error",
+    "af_unpack_q4_g32",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -166,6 +168,7 @@ def lib() -> C.CDLL:
         "af_profile_set": (i, [vp, vp, i]),
         "af_wall_clock_khz": (i, [vp]),
         "af_set_option": (i, [vp, i, i]),
+        "af_unpack_q4_g32": (i, [vp, vp, vp, i, i, i, i, vp, vp]),
         "af_last_device_error": (i, [vp, C.POINTER(i), i]),
         "af_cost_eval": (i, [C.POINTER(CostIn), C.POINTER(CostOut)]),
         "af_plan_search": (i, [C.POINTER(PlanIn), C.POINTER(PlanOut)]),
@@ -287,6 +290,17 @@ class Context:
                                     _ptr(scales, torch.float16, "scales"), ld, col0),
                "af_pack_q4_g32")
         return packed, scales
+
+    def unpack_q4_g32(self, packed, scales, out: int, col0: int = 0):
+        """(q int8 [out][in], w fp32 [out][in]) of the columns col0..col0+out of a packed matrix."""
+        n_in, ld = packed.shape[0], scales.shape[1]
+        q = torch.empty((out, n_in), dtype=torch.int8, device=self.device)
+        w = torch.empty((out, n_in), dtype=torch.float32, device=self.device)
+        _check(lib().af_unpack_q4_g32(self._h, _ptr(packed, torch.uint8, "packed"),
+                                      _ptr(scales, torch.float16, "scales"), out, n_in, ld, col0,
+                                      _ptr(q, torch.int8, "q"), _ptr(w, torch.float32, "w")),
+               "af_unpack_q4_g32")
+        return q, w
 
     def pack_q4_cl(self, W, packed=None, scales=None, ld=None, col0=0):
         """Channel-local groups: scales [in][ld/32]."""

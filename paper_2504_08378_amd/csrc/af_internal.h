@@ -45,6 +45,9 @@ struct af_ctx {
   long long* prof;
   int prof_slots, prof_next;
   int use_layer_kernel;   // af_set_option(AF_OPT_LAYER_KERNEL, 1): one launch per layer
+  int validate;           // af_set_option(AF_OPT_VALIDATE, 1): check caller index lists on the device
+  // launch-shape overrides for tuning sweeps (af_set_option; 0 = the built-in heuristic)
+  int tune_lx, tune_nw, tune_split, tune_wgs, moe_router_kernel;
   int layer_kernel_state; // 0 not probed yet, 1 usable, -1 not usable on this device
 };
 
@@ -147,6 +150,8 @@ struct af_gemv_args {
   float* router_logits;
 };
 int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
+// AF_OPT_VALIDATE: queue the check of a caller's index list (ascending, unique, inside [0, n))
+int af_validate_idx(af_ctx* ctx, const int32_t* idx, int nidx_host, const int32_t* nidx_dev, int n);
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);
 
 // ---- cross-workgroup hand-off without cache-wide fences ------------------------------------
@@ -198,6 +203,14 @@ __device__ __forceinline__ int af_ticket_take(int* t) {
 #endif
 
 #ifdef __HIPCC__
+// A caller-supplied channel index outside [0, n): reported in the device error word (which lies
+// AF_TICKET_ERR ints behind the ticket area the kernel already knows) and replaced by a row
+// that contributes nothing, so no access ever leaves the caller's buffers.
+__device__ __forceinline__ void af_report_bad_index(int* tickets) {
+  __hip_atomic_fetch_or(tickets + AF_TICKET_ERR, (int)AF_DEVERR_IDX, __ATOMIC_RELAXED,
+                        __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Time stamps of a layer kernel (af_profile_set): slot[0] = earliest entry, slot[1] = latest
 // exit over its workgroups, in ticks of the device's constant-rate wall clock.
 __device__ __forceinline__ void af_prof_begin(long long* slot) {

@@ -61,6 +61,24 @@ extern "C" int af_set_option(af_ctx* ctx, int option, int value) {
     case AF_OPT_LAYER_KERNEL:
       ctx->use_layer_kernel = value ? 1 : 0;
       return AF_OK;
+    case AF_OPT_VALIDATE:
+      ctx->validate = value ? 1 : 0;
+      return AF_OK;
+    case AF_OPT_TUNE_LX:
+      ctx->tune_lx = value;
+      return AF_OK;
+    case AF_OPT_TUNE_WAVES:
+      ctx->tune_nw = value;
+      return AF_OK;
+    case AF_OPT_TUNE_SPLIT:
+      ctx->tune_split = value;
+      return AF_OK;
+    case AF_OPT_TUNE_WORKGROUPS:
+      ctx->tune_wgs = value;
+      return AF_OK;
+    case AF_OPT_MOE_ROUTER_KERNEL:
+      ctx->moe_router_kernel = value ? 1 : 0;
+      return AF_OK;
     default:
       return AF_EINVAL;
   }
@@ -77,6 +95,56 @@ extern "C" int af_last_device_error(af_ctx* ctx, int* flags, int clear) {
     const int zero = 0;
     if (hipMemcpy(word, &zero, sizeof(int), hipMemcpyHostToDevice) != hipSuccess) return AF_EHIP;
   }
+  return AF_OK;
+}
+
+// AF_OPT_VALIDATE: every entry of the list inside [0, n) and larger than the one before it.
+__global__ void validate_idx_kernel(const int32_t* idx, int nidx_host, const int32_t* nidx_dev, int n,
+                                    int* err) {
+  int nidx = nidx_host;
+  if (nidx_dev) nidx = min(*nidx_dev, nidx);
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nidx) return;
+  const int j = idx[i];
+  const bool bad = (unsigned)j >= (unsigned)n || (i > 0 && idx[i - 1] >= j);
+  if (bad) __hip_atomic_fetch_or(err, (int)AF_DEVERR_IDX, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+int af_validate_idx(af_ctx* ctx, const int32_t* idx, int nidx_host, const int32_t* nidx_dev, int n) {
+  if (!idx || nidx_host <= 0) return AF_OK;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  int* err = (int*)(ctx->ws + ctx->lay.tickets) + AF_TICKET_ERR;
+  hipLaunchKernelGGL(validate_idx_kernel, dim3((nidx_host + 255) / 256), dim3(256), 0, ctx->stream, idx,
+                     nidx_host, nidx_dev, n, err);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+// Device-side inverse of af_pack_q4_g32: one thread per (input channel, column pair).
+__global__ __launch_bounds__(256) void unpack_q4_kernel(const unsigned char* packed, const half_t* scales,
+                                                        int in, int out, int ld, int col0, signed char* q_out,
+                                                        float* w_out) {
+  const int pair = blockIdx.x * blockDim.x + threadIdx.x;
+  const int j = blockIdx.y;
+  if (pair * 2 >= out) return;
+  const unsigned char b = packed[(size_t)j * (ld / 2) + col0 / 2 + pair];
+  for (int e = 0; e < 2; ++e) {
+    const int o = pair * 2 + e;
+    const int q = (int)((b >> (4 * e)) & 15u) - 8;
+    if (q_out) q_out[(size_t)o * in + j] = (signed char)q;
+    if (w_out) w_out[(size_t)o * in + j] = (float)q * (float)scales[(size_t)(j / 32) * ld + col0 + o];
+  }
+}
+
+extern "C" int af_unpack_q4_g32(af_ctx* ctx, const void* packed, const void* scales_f16, int out, int in,
+                                int ld, int col0, void* q_i8, void* w_f32) {
+  if (!ctx || !packed || !scales_f16 || (!q_i8 && !w_f32)) return AF_ENULL;
+  if (out <= 0 || in <= 0 || col0 < 0) return AF_EINVAL;
+  if (in % 32 || out % 8 || col0 % 8 || ld % 8 || col0 + out > ld || in > 65535) return AF_ESHAPE;
+  dim3 grid((out / 2 + 255) / 256, in);
+  hipLaunchKernelGGL(unpack_q4_kernel, grid, dim3(256), 0, ctx->stream, (const unsigned char*)packed,
+                     (const half_t*)scales_f16, in, out, ld, col0, (signed char*)q_i8, (float*)w_f32);
+  AF_LAUNCH_CHECK();
   return AF_OK;
 }
 

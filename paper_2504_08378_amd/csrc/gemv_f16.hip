@@ -24,8 +24,8 @@
 #include "row_prologue.h"
 #include "gemv_f16_body.h"
 
-// Tile width, waves per workgroup and split count for a shape.  AF_GEMV_LX / AF_GEMV_NW /
-// AF_GEMV_SPLIT / AF_GEMV_WGS in the environment override the heuristic (tuning sweeps).
+// Tile width, waves per workgroup and split count for a shape.  The AF_OPT_TUNE_* options of
+// the context override the heuristic (tuning sweeps).
 static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, int* lx_out,
                           int* nw_out, int* s_out) {
   // Measured on the 7B and 13B operators (cold matrices): 128-column tiles (256 B per row and
@@ -37,26 +37,14 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
   // CU); a plain GEMV prefers several small ones per CU.
   int lx = out <= 16384 ? 16 : 64;
   int nw = selects ? 16 : 4;
-  if (const char* e = getenv("AF_GEMV_LX")) {
-    int v = atoi(e);
-    if (v == 16 || v == 32 || v == 64) lx = v;
-  }
-  if (const char* e = getenv("AF_GEMV_NW")) {
-    int v = atoi(e);
-    if (v == 4 || v == 8 || v == 16) nw = v;
-  }
+  if (ctx->tune_lx == 16 || ctx->tune_lx == 32 || ctx->tune_lx == 64) lx = ctx->tune_lx;
+  if (ctx->tune_nw == 4 || ctx->tune_nw == 8 || ctx->tune_nw == 16) nw = ctx->tune_nw;
   const int per_cu = 16 / nw;  // workgroups of nw waves that one CU holds at a time
   int target_wgs = nw == 4 ? (out <= 4096 ? ctx->n_cu : ctx->n_cu * 4) : ctx->n_cu * per_cu;
-  if (const char* e = getenv("AF_GEMV_WGS")) {
-    int v = atoi(e);
-    if (v > 0) target_wgs = v;
-  }
+  if (ctx->tune_wgs > 0) target_wgs = ctx->tune_wgs;
   const int tiles = (out + lx * 8 - 1) / (lx * 8);
   int S = target_wgs / tiles;  // never more workgroups than the chip holds at once
-  if (const char* e = getenv("AF_GEMV_SPLIT")) {
-    int v = atoi(e);
-    if (v > 0) S = v;
-  }
+  if (ctx->tune_split > 0) S = ctx->tune_split;
   const int min_rows = 32;  // a split shorter than this is mostly reduction overhead
   int max_s = (nidx + min_rows - 1) / min_rows;
   if (max_s < 1) max_s = 1;
@@ -218,8 +206,9 @@ extern "C" int af_sparse_gemv_f16(af_ctx* ctx, const void* Wt, int in, int out, 
                                   const void* x_f16, const int32_t* idx, int nidx_host,
                                   const int32_t* nidx_dev, void* y, int y_kind,
                                   const void* residual_f16) {
-  const int rc = sparse_gemv_f16_check(ctx, Wt, in, out, ld, x_f16, idx, &nidx_host, &nidx_dev, y, y_kind);
+  int rc = sparse_gemv_f16_check(ctx, Wt, in, out, ld, x_f16, idx, &nidx_host, &nidx_dev, y, y_kind);
   if (rc) return rc;
+  if (ctx->validate && (rc = af_validate_idx(ctx, idx, nidx_host, nidx_dev, in))) return rc;
   return sparse_gemv_f16_launch(ctx, Wt, in, out, ld, x_f16, idx, nidx_host, nidx_dev, y, y_kind,
                                 residual_f16);
 }

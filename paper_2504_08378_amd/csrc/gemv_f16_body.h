@@ -275,15 +275,25 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
           const int i = tid + u * GEMV_THREADS;
           if (i < cnt) {
             const int j = pre[u];
-            const unsigned bits = p.use_lds_x() ? xs[j] : xg[j];
-            s_list[i] = ((unsigned)j << 16) | bits;
+            if ((unsigned)j < (unsigned)r.n) {
+              const unsigned bits = p.use_lds_x() ? xs[j] : xg[j];
+              s_list[i] = ((unsigned)j << 16) | bits;
+            } else {  // broken precondition: row 0 times zero, and the error word
+              s_list[i] = 0u;
+              af_report_bad_index(p.tickets);
+            }
           }
         }
       } else {
         for (int i = tid; i < cnt; i += GEMV_THREADS) {
           const int j = r.idx ? r.idx[base + i] : base + i;
-          const unsigned bits = p.use_lds_x() ? xs[j] : xg[j];
-          s_list[i] = ((unsigned)j << 16) | bits;
+          if ((unsigned)j < (unsigned)r.n) {
+            const unsigned bits = p.use_lds_x() ? xs[j] : xg[j];
+            s_list[i] = ((unsigned)j << 16) | bits;
+          } else {
+            s_list[i] = 0u;
+            af_report_bad_index(p.tickets);
+          }
         }
       }
       __syncthreads();

@@ -253,8 +253,13 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
       __syncthreads();
       for (int i = tid; i < cnt; i += THREADS) {
         const int j = r.idx ? r.idx[base + i] : base + i;
-        const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
-        s_list[i] = ((unsigned)j << 16) | bits;
+        if ((unsigned)j < (unsigned)r.n) {
+          const unsigned bits = p.use_lds_x ? xs[j] : xg[j];
+          s_list[i] = ((unsigned)j << 16) | bits;
+        } else {  // broken precondition: row 0 times zero, and the error word
+          s_list[i] = 0u;
+          af_report_bad_index(p.tickets);
+        }
       }
       __syncthreads();
       stream(cnt);
@@ -353,14 +358,8 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   // one 1024-thread workgroup per compute unit measured faster than four 256-thread ones for
   // every form of this kernel (with or without the selecting front end)
   int nw = 16;
-  if (const char* e = getenv("AF_Q4_LX")) {
-    int v = atoi(e);
-    if (v == 16 || v == 32 || v == 64) lx = v;
-  }
-  if (const char* e = getenv("AF_Q4_NW")) {
-    int v = atoi(e);
-    if (v == 4 || v == 16) nw = v;
-  }
+  if (ctx->tune_lx == 16 || ctx->tune_lx == 32 || ctx->tune_lx == 64) lx = ctx->tune_lx;
+  if (ctx->tune_nw == 4 || ctx->tune_nw == 16) nw = ctx->tune_nw;
   const int tw = lx * 8;
   const int n_slots = a.w_sel ? a.n_slots : 1;
   if (n_slots < 1 || a.out % n_slots) return AF_EINVAL;
@@ -371,10 +370,7 @@ int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a) {
   const int out_pad = tiles * tw;
   if (tiles > AF_TICKET_ATTN) return AF_ESHAPE;
   int target = nw == 16 ? ctx->n_cu : ctx->n_cu * 4;
-  if (const char* e = getenv("AF_Q4_WGS")) {
-    int v = atoi(e);
-    if (v > 0) target = v;
-  }
+  if (ctx->tune_wgs > 0) target = ctx->tune_wgs;
   int S = target / tiles;
   int max_s = (max_rows + 63) / 64;
   if (max_s < 1) max_s = 1;
@@ -466,6 +462,10 @@ static int sparse_gemv_q4_any(af_ctx* ctx, bool cl, const void* packed, const vo
   a.y = y;
   a.y_kind = y_kind;
   a.residual = (const half_t*)residual_f16;
+  if (ctx->validate) {
+    const int rc = af_validate_idx(ctx, idx, nidx_host, nidx_dev, in);
+    if (rc) return rc;
+  }
   return af_launch_gemv_q4(ctx, a);
 }
 

@@ -1126,7 +1126,7 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
   }
   // The router runs inside the gate|up launch when that kernel can take it (up to 8 experts,
   // d <= 8192); otherwise as a launch of its own in front of it.
-  const bool fuse_router = mcfg->n_experts <= 8 && d <= 8192 && !getenv("AF_MOE_ROUTER_KERNEL");
+  const bool fuse_router = mcfg->n_experts <= 8 && d <= 8192 && !ctx->moe_router_kernel;
   if (!fuse_router) {
     RouterParams rp{};
     rp.rows.pro = AF_PRO_RMSNORM;

@@ -20,6 +20,7 @@ struct UnionBuildParams {
   int32_t* union_n;        // [1]
   half_t* Xm;              // [in][8]
   int B, k, in;
+  int* tickets;            // the device error word lies behind them
 };
 
 __global__ __launch_bounds__(UB_THREADS) void union_build_kernel(UnionBuildParams p) {
@@ -29,7 +30,13 @@ __global__ __launch_bounds__(UB_THREADS) void union_build_kernel(UnionBuildParam
   for (int j = tid; j < p.in; j += UB_THREADS) s_mask[j] = 0;
   __syncthreads();
   for (int b = 0; b < p.B; ++b)
-    for (int t = tid; t < p.k; t += UB_THREADS) atomicOr(&s_mask[p.idx_b[(size_t)b * p.k + t]], 1u << b);
+    for (int t = tid; t < p.k; t += UB_THREADS) {
+      const int j = p.idx_b[(size_t)b * p.k + t];
+      if ((unsigned)j < (unsigned)p.in)
+        atomicOr(&s_mask[j], 1u << b);
+      else  // broken precondition: the entry is dropped and reported
+        af_report_bad_index(p.tickets);
+    }
   __syncthreads();
   // masked, transposed token values
   for (int j = tid; j < p.in; j += UB_THREADS) {
@@ -238,6 +245,12 @@ extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int
   bp.B = B;
   bp.k = k;
   bp.in = in;
+  bp.tickets = (int*)(ctx->ws + ctx->lay.tickets);
+  if (ctx->validate)
+    for (int b = 0; b < B; ++b) {
+      const int rc = af_validate_idx(ctx, idx_b + (size_t)b * k, k, nullptr, in);
+      if (rc) return rc;
+    }
   static bool lds_attr_set = false;
   if (!lds_attr_set) {  // up to 128 KB of dynamic LDS for the channel masks
     lds_attr_set = true;

@@ -61,6 +61,18 @@ def test_null_context_is_rejected_on_the_host(L):
     assert L.af_create(None, 0, None) == -2
 
 
+def test_option_and_error_word_calls_check_their_arguments(L):
+    null = C.c_void_p(None)
+    one = C.c_void_p(256)
+    flags = C.c_int(0)
+    assert L.af_set_option(null, 1, 1) == -2
+    assert L.af_last_device_error(null, C.byref(flags), 0) == -2
+    assert L.af_unpack_q4_g32(null, one, one, 8, 32, 8, 0, one, one) == -2
+    assert L.af_profile_set(null, one, 4) == -2
+    assert L.af_sparse_gemv_f16_noalloc(null, one, 8, 8, 8, one, one, 4, null, one, 0, null) == -2
+    assert L.af_strerror(-6) not in (b"ok", b"unknown status")
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     from paper_2504_08378_amd import binding as B
     monkeypatch.setattr(B, "_lib", None)

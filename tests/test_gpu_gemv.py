@@ -207,3 +207,37 @@ def test_union_70b_shapes_sampled(ctx, name, out, n, Bt):
         got = ctx.select_topk(to_dev(X[b]), k)
         ctx.synchronize()
         assert np.array_equal(to_host(got), idx_b[b])
+
+
+def test_index_precondition_is_reported_not_followed(ctx):
+    """An index list that breaks its precondition never makes a kernel read outside the
+    caller's buffers: an entry out of range adds nothing and sets AF_DEVERR_IDX; with
+    AF_OPT_VALIDATE an unsorted or repeated list is reported as well."""
+    W, x = _case(136, 100, 11)
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    good = O.select_topk(x, 40)
+    assert ctx.last_device_error() == 0
+    bad = good.copy(); bad[7] = 100; bad[9] = -3            # out of range on both sides
+    y = ctx.sparse_gemv_f16(Wt, to_dev(x), to_dev(bad)); ctx.synchronize()
+    assert ctx.last_device_error() == B.AF_DEVERR_IDX
+    kept = np.delete(good, [7, 9])
+    assert O.rel_err(to_host(y), O.sparse_gemv(W, x, kept)) <= TOL
+    assert ctx.last_device_error() == 0                      # the read above cleared the word
+    # sorted-and-unique is only checked in validate mode
+    rep = good.copy(); rep[5] = rep[4]
+    ctx.sparse_gemv_f16(Wt, to_dev(x), to_dev(rep)); ctx.synchronize()
+    assert ctx.last_device_error() == 0
+    ctx.set_option(B.AF_OPT_VALIDATE, 1)
+    try:
+        ctx.sparse_gemv_f16(Wt, to_dev(x), to_dev(rep)); ctx.synchronize()
+        assert ctx.last_device_error() == B.AF_DEVERR_IDX
+        ctx.sparse_gemv_f16(Wt, to_dev(x), to_dev(good)); ctx.synchronize()
+        assert ctx.last_device_error() == 0
+        # union: a row of the batch with an entry out of range
+        X = np.stack([x, x[::-1].copy()])
+        idx_b = np.stack([good, O.select_topk(X[1], 40)]).astype(np.int32)
+        idx_b[1, 3] = 4000
+        ctx.sparse_gemv_union_f16(Wt, to_dev(X), to_dev(idx_b)); ctx.synchronize()
+        assert ctx.last_device_error() == B.AF_DEVERR_IDX
+    finally:
+        ctx.set_option(B.AF_OPT_VALIDATE, 0)

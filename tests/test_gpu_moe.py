@@ -204,7 +204,7 @@ def test_moe_other_top_counts(ctx, top):
     assert O.rel_err(to_host(hout), tr.hidden, 1.0) <= (TOL if same else 5e-2)
 
 
-def test_router_as_its_own_launch_gives_the_same_layer(ctx, monkeypatch):
+def test_router_as_its_own_launch_gives_the_same_layer(ctx):
     """The router runs inside the gate|up launch by default; the stand-alone router kernel (used
     when that launch cannot take it) must lead to the same experts and the same layer output."""
     shape, cfg, w, K, V, h, widths = _setup("tiny_moe", 11)
@@ -213,11 +213,11 @@ def test_router_as_its_own_launch_gives_the_same_layer(ctx, monkeypatch):
     hin = to_dev(h)
     outs = []
     for separate in (False, True):
-        if separate:
-            monkeypatch.setenv("AF_MOE_ROUTER_KERNEL", "1")
+        ctx.set_option(B.AF_OPT_MOE_ROUTER_KERNEL, 1 if separate else 0)
         hout = torch.zeros_like(hin)
         lay.run(hin, hout, to_dev(K), to_dev(V), KV_LEN, KV_CAP, KV_LEN, M.select_cfg(B.AF_SEL_TOPK, ks))
         ctx.synchronize()
+        ctx.set_option(B.AF_OPT_MOE_ROUTER_KERNEL, 0)
         outs.append((to_host(lay.experts).copy(), to_host(lay.weights).copy(), to_host(lay.logits).copy(),
                      to_host(hout).copy()))
     assert outs[0][0].tolist() == outs[1][0].tolist()

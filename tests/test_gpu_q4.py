@@ -128,3 +128,21 @@ def test_cl_gemv(ctx, out, n, k):
     assert O.rel_err(to_host(y), O.sparse_gemv_q4_cl(nib, s, x, np.arange(n)) + res.astype(np.float64)) <= TOL
     with pytest.raises(B.AfError):
         ctx.sparse_gemv_q4_cl(packed, scales, to_dev(x), None, out=out - 8)      # out % 32 != 0
+
+
+@pytest.mark.parametrize("out,n,col0,ld", [(8, 32, 0, 8), (136, 96, 0, 136), (520, 640, 8, 544)])
+def test_unpack_is_the_inverse_of_pack_on_the_device(ctx, out, n, col0, ld):
+    """af_unpack_q4_g32 reads the packed bytes and scales the way the GEMV kernel does: the
+    integers it returns are the oracle quantiser's, the products are exact in fp32.  A nibble
+    order or a scale index that differed from the documented layout would fail here."""
+    import torch
+    W, _ = _case(out, n, 7)
+    W[1, :32] = 0                                       # a group whose scale is zero
+    packed = torch.zeros((n, ld // 2), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((n // 32, ld), dtype=torch.float16, device="cuda")
+    ctx.pack_q4_g32(to_dev(W), packed, scales, col0=col0)
+    q, w = ctx.unpack_q4_g32(packed, scales, out, col0=col0)
+    ctx.synchronize()
+    nib, s = O.quantize_q4_g32(W)
+    assert np.array_equal(to_host(q).astype(np.int64), nib.astype(np.int64) - 8)
+    assert np.array_equal(to_host(w).astype(np.float64), O.dequant_q4_g32(nib, s))
