@@ -14,7 +14,7 @@ import synth_inputs as S
 from oracle import activeflow_oracle as O
 from paper_2504_08378_amd import binding as B
 from paper_2504_08378_amd import model as M
-from gpu_util import to_dev, to_host  # noqa: F401
+from gpu_util import layer_taps, teacher_forced_layer_errors, to_dev, to_host  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -108,8 +108,15 @@ def test_layer_with_forced_sets(ctx, name, sp):
     assert O.rel_err(t["h_mid"], tr.h_mid) <= TOL
     assert O.rel_err(t["x_gateup"], tr.x[2]) <= TOL
     assert O.rel_err(t["gateup"], tr.gateup) <= TOL
-    assert O.rel_err(t["x_down"], tr.x[3]) <= 2 * TOL      # product of two rounded fp16 tensors
+    # x_down multiplies two tensors that may each differ from the oracle's in the last fp16 bit:
+    # chained, so judged against the rms; the strict bound follows teacher-forced below
+    assert O.rel_err(t["x_down"], tr.x[3], 1.0) <= TOL
     assert O.rel_err(to_host(hout), tr.hidden) <= TOL
+    # every stage on the GPU's own input bits and the forced sets: strict measure, 2e-3
+    errs, _ = teacher_forced_layer_errors(O, _ocfg(shape), layers[0], h, kv[0][0], kv[0][1], KV_LEN, KV_LEN,
+                                          layer_taps(ctx, shape), to_host(hout), tr.idx,
+                                          O.SelectCfg(O.SEL_TOPK, ks))
+    assert max(errs.values()) <= TOL, errs
     # KV append
     assert O.rel_err(to_host(st.K[0])[:, KV_LEN], tr.k_new) <= TOL
     assert np.array_equal(to_host(st.V[0])[:, KV_LEN], to_host(ctx.layer_tap(1, shape.qkv_out))[-shape.n_kv_heads * shape.head_dim:].reshape(shape.n_kv_heads, -1))
@@ -277,7 +284,7 @@ def test_7b_layer_full_size_stage_by_stage(ctx):
         "x_qkv": O.rel_err(t["x_qkv"], tr.x[0]), "qkv": O.rel_err(t["qkv"], tr.qkv),
         "attn": O.rel_err(t["attn"], tr.attn, 1.0), "h_mid": O.rel_err(t["h_mid"], tr.h_mid, 1.0),
         "x_gateup": O.rel_err(t["x_gateup"], tr.x[2], 1.0), "gateup": O.rel_err(t["gateup"], tr.gateup, 1.0),
-        "x_down": O.rel_err(t["x_down"], tr.x[3], 1.0) / 2, "hidden": O.rel_err(to_host(hout), tr.hidden, 1.0),
+        "x_down": O.rel_err(t["x_down"], tr.x[3], 1.0), "hidden": O.rel_err(to_host(hout), tr.hidden, 1.0),
     }
     print("stage errors:", {k: f"{v:.2e}" for k, v in errs.items()})
     assert max(errs.values()) <= TOL, errs
