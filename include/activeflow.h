@@ -437,6 +437,12 @@ int af_plan_search(const af_plan_in* in, af_plan_out* out);
 int af_probe_sink_floats(af_ctx* ctx);
 int af_probe_stream_read(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
                          int wgs_per_cu);
+/* Other shapes of the same reader, so that the yardstick does not rest on one of them: threads
+ * per workgroup (256 or 1024), 16-byte loads in flight per lane (4, 8, 16; non-temporal: 8, 16),
+ * loads marked non-temporal or not; wgs_per_cu * threads <= 8192.  AF_EINVAL for a combination
+ * that is not built. */
+int af_probe_stream_read_variant(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
+                                 int wgs_per_cu, int threads, int in_flight, int nontemporal);
 
 /* Measurement aid: time stamps of the layer kernels.  While a stamp buffer is set, every kernel
  * that af_decode_layer / af_decode_stack / af_decode_moe_layer and the GEMV entry points launch

@@ -38,7 +38,7 @@ EXPORTS = [
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
     "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
     "af_profile_set", "af_wall_clock_khz", "af_set_option", "af_last_device_error",
-    "af_unpack_q4_g32",
+    "af_unpack_q4_g32", "af_probe_stream_read_variant",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -154,6 +154,7 @@ def lib() -> C.CDLL:
         "af_graph_destroy": (i, [vp]),
         "af_probe_sink_floats": (i, [vp]),
         "af_probe_stream_read": (i, [vp, vp, sz, vp, i]),
+        "af_probe_stream_read_variant": (i, [vp, vp, sz, vp, i, i, i, i]),
         "af_calib_accumulate": (i, [vp, vp, i, vp]),
         "af_calib_accumulate_layer": (i, [vp, C.POINTER(LayerCfg), C.POINTER(vp)]),
         "af_calib_thresholds": (i, [vp, vp, C.POINTER(C.c_int), i, vp]),
@@ -488,6 +489,12 @@ class Context:
 
     def graph_destroy(self, g):
         _check(lib().af_graph_destroy(g), "af_graph_destroy")
+
+    def probe_stream_read_variant(self, buf, sink, wgs_per_cu, threads, in_flight, nontemporal):
+        _check(lib().af_probe_stream_read_variant(self._h, _ptr(buf, torch.uint8), buf.numel(),
+                                                  _ptr(sink, torch.float32), wgs_per_cu, threads,
+                                                  in_flight, 1 if nontemporal else 0),
+               "af_probe_stream_read_variant")
 
     # ---- threshold calibration ---------------------------------------------------------
     def calib_hist(self):

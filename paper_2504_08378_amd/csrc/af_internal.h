@@ -211,6 +211,14 @@ __device__ __forceinline__ void af_report_bad_index(int* tickets) {
                         __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// A load of data that is used once (weight rows): marked non-temporal so that it does not
+// displace lines that are used again; a plain streaming read of HBM measured about 10 % faster
+// with this mark (6.7 against 6.05 TB/s).
+template <typename T>
+__device__ __forceinline__ T af_load_once(const T* p) {
+  return __builtin_nontemporal_load(p);
+}
+
 // Time stamps of a layer kernel (af_profile_set): slot[0] = earliest entry, slot[1] = latest
 // exit over its workgroups, in ticks of the device's constant-rate wall clock.
 __device__ __forceinline__ void af_prof_begin(long long* slot) {

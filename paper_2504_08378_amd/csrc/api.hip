@@ -344,6 +344,49 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const probe_f4* __rest
   if (threadIdx.x == 0) sink[blockIdx.x] = s;
 }
 
+// Variants of the plain reader: THREADS per workgroup, U 16-byte loads in flight per lane,
+// NT = loads marked non-temporal (the data is used once).
+template <int THREADS, int U, bool NT>
+__global__ __launch_bounds__(THREADS) void stream_read_variant_kernel(const probe_f4* __restrict__ p,
+                                                                      size_t n16, float* sink) {
+  const size_t stride = (size_t)gridDim.x * THREADS;
+  size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x;
+  probe_f4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (; i + (U - 1) * stride < n16; i += U * stride) {
+    probe_f4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = NT ? __builtin_nontemporal_load(p + i + u * stride) : p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += v[u];
+  }
+  for (; i < n16; i += stride) acc += p[i];
+  float s = af_wave_sum(acc.x + acc.y + acc.z + acc.w);
+  if ((threadIdx.x & 63) == 0) atomicAdd(&sink[blockIdx.x], s);
+}
+
+extern "C" int af_probe_stream_read_variant(af_ctx* ctx, const void* dev_ptr, size_t bytes, void* sink_f32,
+                                            int wgs_per_cu, int threads, int in_flight, int nontemporal) {
+  if (!ctx || !dev_ptr || !sink_f32) return AF_ENULL;
+  if (wgs_per_cu < 1 || wgs_per_cu * threads > 8192) return AF_EINVAL;
+  if (bytes == 0 || bytes % 16 || ((uintptr_t)dev_ptr & 15u)) return AF_ESHAPE;
+  const dim3 grid(ctx->n_cu * wgs_per_cu);
+  const probe_f4* p = (const probe_f4*)dev_ptr;
+  float* sink = (float*)sink_f32;
+  const size_t n16 = bytes / 16;
+#define AF_PROBE(T, U, N)                                                                            \
+  if (threads == T && in_flight == U && (nontemporal != 0) == N) {                                   \
+    hipLaunchKernelGGL((stream_read_variant_kernel<T, U, N>), grid, dim3(T), 0, ctx->stream, p, n16, \
+                       sink);                                                                        \
+    AF_LAUNCH_CHECK();                                                                               \
+    return AF_OK;                                                                                    \
+  }
+  AF_PROBE(256, 4, false) AF_PROBE(256, 8, false) AF_PROBE(256, 16, false)
+  AF_PROBE(1024, 4, false) AF_PROBE(1024, 8, false) AF_PROBE(1024, 16, false)
+  AF_PROBE(256, 8, true) AF_PROBE(256, 16, true) AF_PROBE(1024, 8, true) AF_PROBE(1024, 16, true)
+#undef AF_PROBE
+  return AF_EINVAL;
+}
+
 extern "C" int af_probe_sink_floats(af_ctx* ctx) {
   if (!ctx) return 0;
   return ctx->n_cu * 32;

@@ -217,7 +217,7 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         e[u] = s_list[i + u * STEP];
-        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
+        w[u] = af_load_once(reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld));
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -237,7 +237,7 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
         const bool ok = i + u * STEP < cnt;
         e[u] = ok ? s_list[i + u * STEP] : 0u;
         if (ok) {
-          w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld);
+          w[u] = af_load_once(reinterpret_cast<const half8*>(wcol + (size_t)(e[u] >> 16) * p.ld));
         } else {
 #pragma unroll
           for (int c = 0; c < 8; ++c) w[u][c] = (half_t)0;

@@ -181,7 +181,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         e[u] = s_list[i + u];
-        w[u] = *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes);
+        w[u] = af_load_once(reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes));
         if (CL) {
           sr[u] = scol[(size_t)(e[u] >> 16) * srow];
         } else {
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
       for (int u = 0; u < U; ++u) {
         const bool ok = i + u < iend;
         e[u] = ok ? s_list[i + u] : 0u;
-        w[u] = ok ? *reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes) : 0u;
+        w[u] = ok ? af_load_once(reinterpret_cast<const unsigned*>(wcol + (size_t)(e[u] >> 16) * row_bytes)) : 0u;
         if (CL) sr[u] = ok ? scol[(size_t)(e[u] >> 16) * srow] : (half_t)0;
       }
 #pragma unroll

@@ -75,8 +75,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   for (int u = 0; u < NB; ++u) {
     const int i = kq + u * KPB;
     const bool ok = i < cnt;
-    kv[u] = ok ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
-    vv[u] = ok ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    kv[u] = ok ? af_load_once(reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
+    vv[u] = ok ? af_load_once(reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
   }
 
   if (tid < HD / 2) {
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int i = i0 + u * KPB;
-      k2[u] = i < cnt ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+      k2[u] = i < cnt ? af_load_once(reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) score(k2[u], i0 + u * KPB);
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int i = i0 + u * KPB;
-      v2[u] = i < cnt ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+      v2[u] = i < cnt ? af_load_once(reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
@@ -392,8 +392,8 @@ __device__ __forceinline__ bool attn_phase(const AttnParams& p, int h, int s, in
   for (int u = 0; u < NB; ++u) {
     const int i = kq + u * KPB;
     const bool ok = i < cnt;
-    kv[u] = ok ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
-    vv[u] = ok ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+    kv[u] = ok ? af_load_once(reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
+    vv[u] = ok ? af_load_once(reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
   }
   if (!layer_wait(ready, ready_total, err, s_flag)) return false;
   af_prof_begin(p.prof);
@@ -442,7 +442,7 @@ __device__ __forceinline__ bool attn_phase(const AttnParams& p, int h, int s, in
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int i = i0 + u * KPB;
-      k2[u] = i < cnt ? *reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+      k2[u] = i < cnt ? af_load_once(reinterpret_cast<const half8*>(Kc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) score(k2[u], i0 + u * KPB);
@@ -495,7 +495,7 @@ __device__ __forceinline__ bool attn_phase(const AttnParams& p, int h, int s, in
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int i = i0 + u * KPB;
-      v2[u] = i < cnt ? *reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8) : zero8;
+      v2[u] = i < cnt ? af_load_once(reinterpret_cast<const half8*>(Vc + (size_t)(t0 + i) * HD + lk * 8)) : zero8;
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) {

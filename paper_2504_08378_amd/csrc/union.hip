@@ -129,7 +129,7 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
       half8 w[U];
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld);
+        w[u] = af_load_once(reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld));
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const half8 xm = s_xm[i + u * STEP];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (i + u * STEP < cnt) {
-          w[u] = *reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld);
+          w[u] = af_load_once(reinterpret_cast<const half8*>(wcol + (size_t)s_idx[i + u * STEP] * p.ld));
         } else {
 #pragma unroll
           for (int c = 0; c < 8; ++c) w[u][c] = (half_t)0;
