@@ -35,12 +35,18 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, in
   // ~2 us after the other half.  A kernel that selects for itself (or builds its input
   // vector) repeats that work in every workgroup, so it runs few, large workgroups (one per
   // CU); a plain GEMV prefers several small ones per CU.
+  // Selecting launches (measured again with non-temporal row loads): 256-column tiles for widths
+  // between 8K and 16K columns (the q|k|v operator: 16.5 against 17.4 us), and three quarters of
+  // the compute units as the workgroup target: fewer splits shorten the reduction by more than
+  // the idle compute units cost (o: 11.5 against 11.9 us, gate|up: 21.9 against 22.2 us).
   int lx = out <= 16384 ? 16 : 64;
+  if (selects && out > 8192 && out <= 16384) lx = 32;
   int nw = selects ? 16 : 4;
   if (ctx->tune_lx == 16 || ctx->tune_lx == 32 || ctx->tune_lx == 64) lx = ctx->tune_lx;
   if (ctx->tune_nw == 4 || ctx->tune_nw == 8 || ctx->tune_nw == 16) nw = ctx->tune_nw;
   const int per_cu = 16 / nw;  // workgroups of nw waves that one CU holds at a time
   int target_wgs = nw == 4 ? (out <= 4096 ? ctx->n_cu : ctx->n_cu * 4) : ctx->n_cu * per_cu;
+  if (nw == 16 && selects) target_wgs = ctx->n_cu * 3 / 4;
   if (ctx->tune_wgs > 0) target_wgs = ctx->tune_wgs;
   const int tiles = (out + lx * 8 - 1) / (lx * 8);
   int S = target_wgs / tiles;  // never more workgroups than the chip holds at once

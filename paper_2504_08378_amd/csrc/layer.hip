@@ -617,15 +617,15 @@ __device__ __forceinline__ bool layer_gemv_phase(const LayerParams& P, int w, un
   return true;
 }
 
-// LX_GU: lanes across a tile of the gate|up operator (its rows are the longest); the other
-// operators use 16 (128-column tiles).
-template <int LX_GU>
+// LX_QKV, LX_GU: lanes across a tile of the q|k|v and the gate|up operator (the wide ones); o and
+// down use 16 (128-column tiles).
+template <int LX_QKV, int LX_GU>
 __global__ __launch_bounds__(LAYER_THREADS) void layer_f16_kernel(LayerParams P) {
   extern __shared__ __align__(16) unsigned short xs[];
   __shared__ GemvLds<LAYER_WAVES> lds;
   __shared__ int s_flag;
   const int w = blockIdx.x;
-  if (!layer_gemv_phase<16, 0, 0>(P, w, xs, lds, s_flag)) return;
+  if (!layer_gemv_phase<LX_QKV, 0, 0>(P, w, xs, lds, s_flag)) return;
   if (w < P.at.n_heads * P.KS) {
     const int h = w % P.at.n_heads, s = w / P.at.n_heads;
     bool ok;
@@ -689,8 +689,9 @@ static int launch_layer_kernel(af_ctx* ctx, const af_layer_cfg* cfg, const af_ge
     // every workgroup of the grid has to be resident at the same time: one per compute unit
     int per_cu = 0;
     bool ok = true;
-    const void* fns[2] = {reinterpret_cast<const void*>(layer_f16_kernel<16>),
-                          reinterpret_cast<const void*>(layer_f16_kernel<64>)};
+    const void* fns[3] = {reinterpret_cast<const void*>(layer_f16_kernel<16, 16>),
+                          reinterpret_cast<const void*>(layer_f16_kernel<16, 64>),
+                          reinterpret_cast<const void*>(layer_f16_kernel<32, 64>)};
     for (const void* fn : fns) {
       per_cu = 0;
       if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET) != hipSuccess ||
@@ -720,7 +721,7 @@ static int launch_layer_kernel(af_ctx* ctx, const af_layer_cfg* cfg, const af_ge
     P.tiles[op] = plan.tiles;
     P.S[op] = plan.S;
     P.lx[op] = plan.lx;
-    if (plan.lx != 16 && !(op == 2 && plan.lx == 64)) return 1;  // the tile shapes the kernel is built for
+    if ((op == 1 || op == 3) && plan.lx != 16) return 1;  // the tile shapes the kernel is built for
     if (plan.lds > lds) lds = plan.lds;
     if (plan.tiles * plan.S > n_wg) n_wg = plan.tiles * plan.S;
   }
@@ -764,10 +765,14 @@ static int launch_layer_kernel(af_ctx* ctx, const af_layer_cfg* cfg, const af_ge
   P.g[0].prof = af_prof_take(ctx);
   a.prof = af_prof_take(ctx);
   for (int op = 1; op < 4; ++op) P.g[op].prof = af_prof_take(ctx);
-  if (P.lx[2] == 64)
-    hipLaunchKernelGGL(layer_f16_kernel<64>, dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+  if (P.lx[0] == 16 && P.lx[2] == 16)
+    hipLaunchKernelGGL((layer_f16_kernel<16, 16>), dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+  else if (P.lx[0] == 16 && P.lx[2] == 64)
+    hipLaunchKernelGGL((layer_f16_kernel<16, 64>), dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+  else if (P.lx[0] == 32 && P.lx[2] == 64)
+    hipLaunchKernelGGL((layer_f16_kernel<32, 64>), dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
   else
-    hipLaunchKernelGGL(layer_f16_kernel<16>, dim3(n_wg), dim3(LAYER_THREADS), lds, ctx->stream, P);
+    return 1;
   AF_LAUNCH_CHECK();
   return AF_OK;
 }
