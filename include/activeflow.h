@@ -388,7 +388,7 @@ int af_lfu_stats(const af_lfu* c, long long* tokens, long long* needed, long lon
                  long long* evictions);
 int af_lfu_cached(const af_lfu* c, int32_t* channels /* capacity entries or NULL */, int* n_cached);
 
-/* Cost model, Section 4.3, Eq. 1-9 as printed (bytes, bytes/s, seconds):
+/* Cost model, Section 4.1, Eq. 1-9 as printed (bytes, bytes/s, seconds):
  *   M_cl = S_l (1-sp) N;  T_load = M_cl (1-hr) / bw_flash_small;  T_comp = M_cl / bw_mem;
  *   T_onload = S_l (1-sp)(1-hr)(1-si) / bw_flash_small;  T_preload = M_cl (1-hr) / bw_flash_large;
  *   T_overlap = T_onload + max(T_preload, T_comp);  T_decode = T_load + T_overlap + T_comp;
@@ -405,7 +405,7 @@ typedef struct {
 } af_cost_out;
 int af_cost_eval(const af_cost_in* in, af_cost_out* out);
 
-/* Greedy search of Section 4.3: sp = 1 - M_max / S_m (clamped to [0, 1)); N = 1, 2, ... with
+/* Greedy search of Section 4.1: sp = 1 - M_max / S_m (clamped to [0, 1)); N = 1, 2, ... with
  * the cache taking what the budget leaves (M_cache = M_max - M_cl - M_kv) and its hit rate read
  * off the caller's curve at M_cache / (S_m (1-sp)) (n_hr points, ascending fractions, linear in
  * between, flat outside); stops when the budget is exhausted, when T_preload <= T_comp, or when

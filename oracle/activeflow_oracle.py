@@ -522,7 +522,7 @@ def rel_err(got, ref, floor_frac: float = 0.01) -> float:
 
 
 # --------------------------------------------------------------------------
-# dynamic weight caching (Section 4.2) and the cost model (Section 4.3)
+# dynamic weight caching (Section 4.2) and the cost model (Section 4.1)
 # --------------------------------------------------------------------------
 class LfuCache:
     """Least-frequently-used cache of weight channels of one tensor (Section 4.2,
@@ -577,7 +577,7 @@ class LfuCache:
 
 
 def cost_model(sp, hr, si, bw_mem, bw_flash_small, bw_flash_large, S_l, N, M_cache, M_kv):
-    """Eq. 1-9 of Section 4.3 as printed (the prose around them names two terms wrongly;
+    """Eq. 1-9 of Section 4.1 as printed (the prose around them names two terms wrongly;
     the equations are taken).  Sizes in bytes, bandwidths in bytes/s, times in seconds.
     Returns a dict with M_cl, M, T_load, T_comp, T_onload, T_preload, T_overlap, T_decode."""
     M_cl = S_l * (1.0 - sp) * N                                   # Eq. 9
@@ -593,7 +593,7 @@ def cost_model(sp, hr, si, bw_mem, bw_flash_small, bw_flash_large, S_l, N, M_cac
 
 def plan_search(M_max, S_m, S_l, M_kv, si, bw_mem, bw_flash_small, bw_flash_large, hr_of_fraction,
                 n_max=64, min_gain=0.0):
-    """Greedy parameter search of Section 4.3 ("Preload-and-computation-balanced cross-layer
+    """Greedy parameter search of Section 4.1 ("Preload-and-computation-balanced cross-layer
     group search").  sp = 1 - M_max / S_m (clamped to [0, 1)); then N = 1, 2, ...: the group
     takes M_cl (Eq. 9), the cache gets what the budget leaves, M_cache = M_max - M_cl - M_kv
     (Eq. 2 and 8 with equality), its hit rate is hr_of_fraction(M_cache / (S_m (1 - sp))), a

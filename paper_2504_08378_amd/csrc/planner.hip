@@ -1,5 +1,5 @@
 // Host-side tools around the hot path: the dynamic weight-cache simulator of Section 4.2 and the
-// cost model with its greedy parameter search of Section 4.3 (Eq. 1-9).  Plain C++ on host
+// cost model with its greedy parameter search of Section 4.1 (Eq. 1-9).  Plain C++ on host
 // memory; no device code.
 #include <algorithm>
 #include <math.h>
@@ -125,7 +125,7 @@ extern "C" int af_lfu_cached(const af_lfu* c, int32_t* channels, int* n_cached) 
   return AF_OK;
 }
 
-// ---- cost model (Section 4.3, Eq. 1-9) ---------------------------------------------------------
+// ---- cost model (Section 4.1, Eq. 1-9) ---------------------------------------------------------
 extern "C" int af_cost_eval(const af_cost_in* in, af_cost_out* out) {
   if (!in || !out) return AF_ENULL;
   if (!(in->bw_mem > 0) || !(in->bw_flash_small > 0) || !(in->bw_flash_large > 0)) return AF_EINVAL;

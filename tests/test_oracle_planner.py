@@ -1,4 +1,4 @@
-"""Pins for the oracle's weight-cache simulator (Section 4.2) and cost model (Section 4.3):
+"""Pins for the oracle's weight-cache simulator (Section 4.2) and cost model (Section 4.1):
 the paper's worked cache example, hand-worked equations, limiting cases and scaling laws."""
 import math
 import os
