@@ -24,11 +24,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the dominant kernel (fused gate|up GEMV, 7B shape, 50 %) from the
-# two rocprofv3 --pmc runs summarised in profiles/gateup_7b_f16_sp50_pmc_traffic.md:
-# FETCH_SIZE 44452.9 KiB x 2.000 + WRITE_SIZE 497.2 KiB x 1.000, the factors being what the same
-# counters read for a plain 256 MiB device copy (131083.5 and 262144.0 KiB).
-TRAFFIC_BYTES_PER_LAUNCH = {("7b", "f16", 50): int((44452.9 * 2.0 + 497.2) * 1024)}
+# HBM bytes per launch of the dominant kernel (fused gate|up GEMV, 7B shape, 50 %).  Counters
+# cannot be read from inside this process; the figure comes from the two rocprofv3 --pmc runs
+# of this very command that profiles/gateup_7b_f16_sp50_pmc_traffic.md summarises (file, kernel
+# name and launch shape are repeated in the output so that a stale figure shows):
+# FETCH_SIZE KiB x fetch factor + WRITE_SIZE KiB x write factor, the factors being what the same
+# counters read for a plain 256 MiB device copy of known size.
+TRAFFIC = {("7b", "f16", 50): {"fetch_KiB": 44415.6, "fetch_factor": 2.000, "write_KiB": 409.8, "write_factor": 1.000,
+                               "kernel": "gemv_f16_kernel<64, 8, 16, false> grid 43x4",
+                               "source": "profiles/gateup_7b_f16_sp50_pmc_traffic.md"}}
 
 
 def keep_count(n: int, sp: int) -> int:
@@ -643,9 +647,15 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": kname,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.shape, args.weights, sp))
-                if L == base.n_layers and args.group == 1 and keep_frac is None else None,
+                "traffic": None,
                 "bytes_per_launch": alg, "us_per_launch": round(us_per_launch, 3), "launches": launches}
+
+    tr_ = TRAFFIC.get((args.shape, args.weights, sp))
+    if tr_ is not None and L == base.n_layers and args.group == 1 and keep_frac is None:
+        roofline["traffic"] = int((tr_["fetch_KiB"] * tr_["fetch_factor"] + tr_["write_KiB"] * tr_["write_factor"]) * 1024)
+        roofline["traffic_source"] = {k_: tr_[k_] for k_ in ("source", "kernel", "fetch_KiB", "fetch_factor",
+                                                             "write_KiB", "write_factor")}
+        roofline["traffic_over_algorithmic"] = round(roofline["traffic"] / alg, 4)
 
     # ---- the box's plain streaming-read rate (what an ideal reader of these bytes gets) ----
     probe = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")
@@ -716,6 +726,25 @@ def main() -> int:
             if n_done == 1:
                 first = tr
         cpu_tok_s = 1.0 / (t_cpu / n_done * L)
+        # a second CPU figure, so that the speed-up is not only "GPU against a dense CPU loop":
+        # the four gathered products of the layer (active columns only, fp32 BLAS) in plain NumPy
+        gathered = None
+        if kind == B.AF_W_F16 and first is not None:
+            mats = [np.concatenate([host_layer0["Wq"], host_layer0["Wk"], host_layer0["Wv"]]), host_layer0["Wo"],
+                    np.concatenate([host_layer0["Wgate"], host_layer0["Wup"]]), host_layer0["Wdown"]]
+            mats = [m_.astype(np.float32) for m_ in mats]
+            xs_ = [np.asarray(v_, dtype=np.float32) for v_ in first.x]
+            t_g, n_g = 0.0, 0
+            while n_g < 20 and t_g < 4.0:
+                t1 = time.perf_counter()
+                for m_, x_, i_ in zip(mats, xs_, first.idx):
+                    _ = m_[:, i_] @ x_[i_]
+                t_g += time.perf_counter() - t1
+                n_g += 1
+            gathered = {"value": round(1.0 / (t_g / n_g * L), 3), "unit": "tokens/s",
+                        "what": "the four gathered fp32 products W[:, idx] @ x[idx] of layer 0 in NumPy "
+                                f"({n_g}x, {t_g:.1f} s), scaled to {L} layers; linear operators only"}
+            del mats
         cpu = {"value": round(cpu_tok_s, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": f"layer 0 of the stack decoded {n_done}x by the fp64 NumPy oracle "
                          f"({t_cpu:.1f} s), scaled to {L} layers"}
@@ -732,6 +761,8 @@ def main() -> int:
         ctx.synchronize()
         err = O.rel_err(st.hidden_out.cpu().numpy(), first.hidden, 1.0)   # chained stages: rms floor
         cpu["gpu_vs_oracle_rel_err_layer0"] = float(f"{err:.3e}")
+        if gathered is not None:
+            cpu["gathered_columns_numpy"] = gathered
         if err > 2e-3:
             print(f"bench.py: WARNING layer-0 output differs from the oracle: {err}", file=sys.stderr)
 
@@ -814,6 +845,14 @@ def main() -> int:
         wl += f", threshold selection calibrated on {args.calib_tokens} tokens (no index lists)"
     if args.group > 1:
         wl += f", index reuse in groups of {args.group} (points mask {args.reuse_points:#06b})"
+    clocks = None
+    try:   # best effort; a child process, never an exec from this one
+        import subprocess
+        smi = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+        clocks = {ln.split(":")[1].strip().split()[0]: ln.split("(")[-1].rstrip(")\n ")
+                  for ln in smi.splitlines() if "clock level" in ln and ("sclk" in ln or "mclk" in ln or "fclk" in ln)}
+    except Exception:
+        pass
     out = {
         "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
         "value": round(tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -830,6 +869,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if clocks:
+        out["clocks_after_run"] = clocks
     if per_op is not None:
         out["per_op"] = per_op
         out["per_op_note"] = ("mean over the layers of one graph replay, median over 10 replays; us = first "
