@@ -26,30 +26,47 @@
 
 // Tile width, waves per workgroup and split count for a shape.  The AF_OPT_TUNE_* options of
 // the context override the heuristic (tuning sweeps).
-static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, int* lx_out,
-                          int* nw_out, int* s_out) {
-  // Measured on the 7B and 13B operators (cold matrices): 128-column tiles (256 B per row and
-  // workgroup) win up to ~16K columns, 512-column tiles (1 KB) beyond.  With 256-column tiles
-  // on a row stride that is a multiple of 1 KB every workgroup stays on one value of address
-  // bit 9 for all its rows, and the half of the workgroups on one of the two values finished
-  // ~2 us after the other half.  A kernel that selects for itself (or builds its input
-  // vector) repeats that work in every workgroup, so it runs few, large workgroups (one per
-  // CU); a plain GEMV prefers several small ones per CU.
-  // Selecting launches (measured again with non-temporal row loads): 256-column tiles for widths
-  // between 8K and 16K columns (the q|k|v operator: 16.5 against 17.4 us), and three quarters of
-  // the compute units as the workgroup target: fewer splits shorten the reduction by more than
-  // the idle compute units cost (o: 11.5 against 11.9 us, gate|up: 21.9 against 22.2 us).
+static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, bool whole_layer,
+                          int* lx_out, int* nw_out, int* s_out) {
+  // A kernel that selects for itself (or builds its input vector) repeats that work in every
+  // workgroup, so it runs few, large workgroups (one 1024-thread workgroup per CU); a plain
+  // GEMV prefers several small ones per CU.
+  //
+  // Selecting launches, measured over the q|k|v, o, gate|up and down operators of the 7B, 13B
+  // and 70B shapes with cold matrices and non-temporal row loads:
+  //  * tile width: 128 columns up to ~6K output columns, 256 up to ~12K, 512 beyond (within
+  //    1-2 % of the best of the three for every operator);
+  //  * splits: between three quarters of the CUs and all of them, the most that leave every
+  //    workgroup 320 rows (128-column tiles) or 500 rows (wider tiles); below that a workgroup
+  //    is mostly front end and reduction.  13B: o 13.1 against 14.6 us, gate|up 31.0 against
+  //    33.5 us, down 24.4 against 26.4 us for 240 against 160 workgroups; 70B down 54.9 against
+  //    58.9 us; Mixtral gate|up of two experts 43 against 53 us (224 against 112 workgroups);
+  //    7B o: 11.7 us with 6 splits, 12.1 with 8; 7B gate|up inside the stack: 21.8 us with 4
+  //    splits, 22.2 with 5.
+  // Plain launches: 128-column tiles up to 16K columns and 512 beyond; with 256-column tiles on
+  // a row stride that is a multiple of 1 KB every workgroup stays on one value of address bit 9
+  // for all its rows, and the half of the workgroups on one of the two values finished ~2 us
+  // after the other half.
   int lx = out <= 16384 ? 16 : 64;
-  if (selects && out > 8192 && out <= 16384) lx = 32;
   int nw = selects ? 16 : 4;
+  if (selects && !whole_layer) lx = out <= 6144 ? 16 : (out <= 12288 ? 32 : 64);
+  if (selects && whole_layer && out > 8192 && out <= 16384) lx = 32;  // the shapes that kernel is built for
   if (ctx->tune_lx == 16 || ctx->tune_lx == 32 || ctx->tune_lx == 64) lx = ctx->tune_lx;
   if (ctx->tune_nw == 4 || ctx->tune_nw == 8 || ctx->tune_nw == 16) nw = ctx->tune_nw;
   const int per_cu = 16 / nw;  // workgroups of nw waves that one CU holds at a time
   int target_wgs = nw == 4 ? (out <= 4096 ? ctx->n_cu : ctx->n_cu * 4) : ctx->n_cu * per_cu;
-  if (nw == 16 && selects) target_wgs = ctx->n_cu * 3 / 4;
+  if (nw == 16 && selects && whole_layer) target_wgs = ctx->n_cu * 3 / 4;
   if (ctx->tune_wgs > 0) target_wgs = ctx->tune_wgs;
   const int tiles = (out + lx * 8 - 1) / (lx * 8);
   int S = target_wgs / tiles;  // never more workgroups than the chip holds at once
+  if (nw == 16 && selects && !whole_layer && ctx->tune_wgs <= 0) {
+    int s_min = ctx->n_cu * 3 / 4 / tiles;
+    if (s_min < 1) s_min = 1;
+    if (tiles * s_min < ctx->n_cu * 6 / 10 && tiles * (s_min + 1) <= ctx->n_cu) ++s_min;
+    const int rows_min = lx == 16 ? 320 : 500;
+    while (S > s_min && nidx / S < rows_min) --S;
+    if (S < s_min) S = s_min;
+  }
   if (ctx->tune_split > 0) S = ctx->tune_split;
   const int min_rows = 32;  // a split shorter than this is mostly reduction overhead
   int max_s = (nidx + min_rows - 1) / min_rows;
@@ -93,8 +110,9 @@ int af_plan_gemv_f16(af_ctx* ctx, const af_gemv_args& a, bool whole_layer, GemvP
   int lx, nw, S;
   // inside the whole-layer kernel every operator runs on the kernel's 1024-thread workgroups,
   // one per compute unit
-  choose_config(ctx, a.out, max_rows,
-                whole_layer || r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, &lx, &nw, &S);
+  // a threshold keeps an unknown number of rows: plan the launch for half of them
+  choose_config(ctx, a.out, r.sel == AF_SEL_THRESHOLD ? (r.n + 1) / 2 : max_rows,
+                whole_layer || r.sel != AF_ROWS_GIVEN || r.pro != AF_PRO_NONE, whole_layer, &lx, &nw, &S);
   const int tw = lx * 8;
   // output slots (one per device-selected matrix; a single one otherwise), whole tiles each
   const int n_slots = a.w_sel ? a.n_slots : 1;
