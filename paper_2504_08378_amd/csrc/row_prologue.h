@@ -10,6 +10,15 @@
 
 #define RP_HIST_COPIES 8
 #define RP_SCRATCH_WORDS (384 * RP_HIST_COPIES)  // 12 KB: both digit tables; reused by the caller afterwards
+// Elements per LDS / global access of the element passes.  With 4 a 4096-wide input gives every
+// one of 1024 threads one vector; with 8 half of the threads would idle while the others walk
+// twice as many elements one after the other, and those serial walks are what the front end
+// spends its time in.
+#ifndef RP_EV
+#define RP_EV 4
+#endif
+typedef _Float16 rp_half __attribute__((ext_vector_type(RP_EV)));
+typedef unsigned short rp_u16 __attribute__((ext_vector_type(RP_EV)));
 
 template <int THREADS>
 struct RowPrologue {
@@ -37,17 +46,16 @@ struct RowPrologue {
     for (int i = threadIdx.x; i < RP_SCRATCH_WORDS; i += THREADS) hist[i] = 0;
   }
 
-  // first-digit counts of one 8-element vector into this lane's replica
-  static __device__ __forceinline__ void count_digit1(unsigned* hist, const half8& h) {
-    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-    const u16x8 b = __builtin_bit_cast(u16x8, h);
+  // first-digit counts of one vector into this lane's replica
+  static __device__ __forceinline__ void count_digit1(unsigned* hist, const rp_half& h) {
+    const rp_u16 b = __builtin_bit_cast(rp_u16, h);
     const int rep = threadIdx.x & (RP_HIST_COPIES - 1);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
+    for (int c = 0; c < RP_EV; ++c) atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
   }
 
   // Fill xs[0..n) with the fp16 bits of the operator input (n % 8 == 0).  Global reads are
-  // 16-byte vectors issued four at a time, so a thread waits for memory once per batch and
+  // RP_EV-element vectors issued four at a time, so a thread waits for memory once per batch and
   // not once per element.
   // `hist`, when given (top-k selection follows), receives the histogram of the first radix
   // digit on the way: the values are counted while they are still in registers, which saves
@@ -56,20 +64,20 @@ struct RowPrologue {
                                                  bool store_x, int store_phase, int store_stride,
                                                  unsigned* hist = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = r.n, nvec = n >> 3;
+    const int n = r.n, nvec = n / RP_EV;
     constexpr int B = 4;
-    half8* xv = reinterpret_cast<half8*>(xs);
-    const half8* src = reinterpret_cast<const half8*>(r.src);
-    half8 zero;
+    rp_half* xv = reinterpret_cast<rp_half*>(xs);
+    const rp_half* src = reinterpret_cast<const rp_half*>(r.src);
+    rp_half zero;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) zero[c] = (half_t)0;
+    for (int c = 0; c < RP_EV; ++c) zero[c] = (half_t)0;
     if (hist != nullptr) {
       zero_hist(hist);
       if (r.pro != AF_PRO_RMSNORM) __syncthreads();  // the norm has a barrier of its own before it counts
     }
     if (r.pro == AF_PRO_NONE) {
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
-        half8 t[B];
+        rp_half t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
 #pragma unroll
@@ -80,15 +88,15 @@ struct RowPrologue {
           }
       }
     } else if (r.pro == AF_PRO_RMSNORM) {
-      const half8* gain = reinterpret_cast<const half8*>(r.gain);
+      const rp_half* gain = reinterpret_cast<const rp_half*>(r.gain);
       // When one batch per thread covers the vector (the usual case) the gains are fetched
       // together with the source, so the sum-of-squares reduction does not sit between two
       // dependent global round trips.
       const bool single = nvec <= B * THREADS;
-      half8 g[B];
+      rp_half g[B];
       float ss = 0.f;
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
-        half8 t[B];
+        rp_half t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
         if (single) {
@@ -98,7 +106,7 @@ struct RowPrologue {
 #pragma unroll
         for (int u = 0; u < B; ++u) {
 #pragma unroll
-          for (int c = 0; c < 8; ++c) ss += (float)t[u][c] * (float)t[u][c];
+          for (int c = 0; c < RP_EV; ++c) ss += (float)t[u][c] * (float)t[u][c];
           if (v0 + u * THREADS < nvec) xv[v0 + u * THREADS] = t[u];  // raw; normalised below
         }
       }
@@ -117,18 +125,18 @@ struct RowPrologue {
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           if (v0 + u * THREADS < nvec) {
-            half8 h = xv[v0 + u * THREADS];   // each thread revisits the vectors it wrote
+            rp_half h = xv[v0 + u * THREADS];   // each thread revisits the vectors it wrote
 #pragma unroll
-            for (int c = 0; c < 8; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
+            for (int c = 0; c < RP_EV; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
             xv[v0 + u * THREADS] = h;
             if (hist != nullptr) count_digit1(hist, h);
           }
         }
       }
     } else {  // AF_PRO_SILUMUL: src = gate[n] | up[n]
-      const half8* up = reinterpret_cast<const half8*>(r.src + n);
+      const rp_half* up = reinterpret_cast<const rp_half*>(r.src + n);
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
-        half8 g[B], u8[B];
+        rp_half g[B], u8[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           const bool ok = v0 + u * THREADS < nvec;
@@ -138,9 +146,9 @@ struct RowPrologue {
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           if (v0 + u * THREADS < nvec) {
-            half8 h;
+            rp_half h;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
+            for (int c = 0; c < RP_EV; ++c) {
               const float gg = (float)g[u][c];
               h[c] = (half_t)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * (float)u8[u][c]);
             }
@@ -152,7 +160,7 @@ struct RowPrologue {
     }
     __syncthreads();
     if (store_x && r.x_out != nullptr) {
-      half8* dst = reinterpret_cast<half8*>(r.x_out);
+      rp_half* dst = reinterpret_cast<rp_half*>(r.x_out);
       for (int v = store_phase * THREADS + tid; v < nvec; v += store_stride * THREADS) dst[v] = xv[v];
     }
   }
@@ -221,29 +229,29 @@ struct RowPrologue {
 
   // Threshold selection without an index list for the whole vector (Section 6: a channel is
   // active iff its magnitude passes the preloaded threshold, which needs no look at any other
-  // channel).  The channels are cut into S contiguous ranges of whole 8-element vectors;
-  // workgroup s builds x only for its range, in xs[0 .. 8 * vectors of the range), and lists
+  // channel).  The channels are cut into S contiguous ranges of whole RP_EV-element vectors;
+  // workgroup s builds x only for its range, in xs[0 .. RP_EV * vectors of the range), and lists
   // the channels of that range that pass, as (index << 16 | fp16 bits).  RMSNorm still reads
   // the whole source once for the sum of squares.  Returns the number of list entries.
-  // The caller guarantees 8 * ceil(n / 8 / S) <= capacity of `list`.
+  // The caller guarantees RP_EV * ceil(n / RP_EV / S) <= capacity of `list` (8 * ceil(n / 8 / S)
+  // is at least that).
   static __device__ __forceinline__ int threshold_range(const af_row_src& r, unsigned short* xs,
                                                         Smem& sm, unsigned* list, int S, int s,
                                                         bool store_x) {
-    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = r.n, nvec = n >> 3;
+    const int n = r.n, nvec = n / RP_EV;
     const int V = (nvec + S - 1) / S;
     const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec), nv = vs1 - vs0;
     constexpr int B = 4;
-    half8* xv = reinterpret_cast<half8*>(xs);
-    const half8* src = reinterpret_cast<const half8*>(r.src);
-    half8 zero;
+    rp_half* xv = reinterpret_cast<rp_half*>(xs);
+    const rp_half* src = reinterpret_cast<const rp_half*>(r.src);
+    rp_half zero;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) zero[c] = (half_t)0;
+    for (int c = 0; c < RP_EV; ++c) zero[c] = (half_t)0;
 
     if (r.pro == AF_PRO_NONE) {
       for (int i0 = tid; i0 < nv; i0 += B * THREADS) {
-        half8 t[B];
+        rp_half t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) t[u] = (i0 + u * THREADS < nv) ? src[vs0 + i0 + u * THREADS] : zero;
 #pragma unroll
@@ -251,9 +259,9 @@ struct RowPrologue {
           if (i0 + u * THREADS < nv) xv[i0 + u * THREADS] = t[u];
       }
     } else if (r.pro == AF_PRO_SILUMUL) {
-      const half8* up = reinterpret_cast<const half8*>(r.src + n);
+      const rp_half* up = reinterpret_cast<const rp_half*>(r.src + n);
       for (int i0 = tid; i0 < nv; i0 += B * THREADS) {
-        half8 g[B], u8[B];
+        rp_half g[B], u8[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           const bool ok = i0 + u * THREADS < nv;
@@ -263,9 +271,9 @@ struct RowPrologue {
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           if (i0 + u * THREADS < nv) {
-            half8 h;
+            rp_half h;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
+            for (int c = 0; c < RP_EV; ++c) {
               const float gg = (float)g[u][c];
               h[c] = (half_t)(gg * __builtin_amdgcn_rcpf(1.0f + __expf(-gg)) * (float)u8[u][c]);
             }
@@ -274,13 +282,13 @@ struct RowPrologue {
         }
       }
     } else {  // AF_PRO_RMSNORM
-      const half8* gain = reinterpret_cast<const half8*>(r.gain);
+      const rp_half* gain = reinterpret_cast<const rp_half*>(r.gain);
       // the range's own vectors (raw) and their gains travel with the first batch of the
       // full pass, so there is one global round trip before the reduction
       const bool single = nv <= B * THREADS;
-      half8 g[B];
+      rp_half g[B];
       if (single) {
-        half8 t[B];
+        rp_half t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           const bool ok = tid + u * THREADS < nv;
@@ -295,13 +303,13 @@ struct RowPrologue {
       }
       float ss = 0.f;
       for (int v0 = tid; v0 < nvec; v0 += B * THREADS) {
-        half8 t[B];
+        rp_half t[B];
 #pragma unroll
         for (int u = 0; u < B; ++u) t[u] = (v0 + u * THREADS < nvec) ? src[v0 + u * THREADS] : zero;
 #pragma unroll
         for (int u = 0; u < B; ++u) {
 #pragma unroll
-          for (int c = 0; c < 8; ++c) ss += (float)t[u][c] * (float)t[u][c];
+          for (int c = 0; c < RP_EV; ++c) ss += (float)t[u][c] * (float)t[u][c];
         }
       }
       ss = af_wave_sum(ss);
@@ -319,9 +327,9 @@ struct RowPrologue {
 #pragma unroll
         for (int u = 0; u < B; ++u) {
           if (i0 + u * THREADS < nv) {
-            half8 h = xv[i0 + u * THREADS];   // each thread revisits the vectors it wrote
+            rp_half h = xv[i0 + u * THREADS];   // each thread revisits the vectors it wrote
 #pragma unroll
-            for (int c = 0; c < 8; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
+            for (int c = 0; c < RP_EV; ++c) h[c] = (half_t)((float)h[c] * scale * (float)g[u][c]);
             xv[i0 + u * THREADS] = h;
           }
         }
@@ -329,7 +337,7 @@ struct RowPrologue {
     }
     __syncthreads();
     if (store_x && r.x_out != nullptr) {
-      half8* dst = reinterpret_cast<half8*>(r.x_out);
+      rp_half* dst = reinterpret_cast<rp_half*>(r.x_out);
       for (int i = tid; i < nv; i += THREADS) dst[vs0 + i] = xv[i];
     }
 
@@ -340,17 +348,16 @@ struct RowPrologue {
   // them is vector vs0 of the operator input.  Every thread owns a contiguous run.
   static __device__ __forceinline__ int range_list(const af_row_src& r, const unsigned short* xs,
                                                    Smem& sm, unsigned* list, int vs0, int nv) {
-    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
     const int tid = threadIdx.x;
     const int T = threshold_key(r.t);
     const int cv = (nv + THREADS - 1) / THREADS;
     const int v0 = min(tid * cv, nv), v1 = min(v0 + cv, nv);
-    const u16x8* xb = reinterpret_cast<const u16x8*>(xs);
+    const rp_u16* xb = reinterpret_cast<const rp_u16*>(xs);
     unsigned gt = 0;
     for (int v = v0; v < v1; ++v) {
-      const u16x8 b = xb[v];
+      const rp_u16 b = xb[v];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < RP_EV; ++c) {
         const unsigned key = b[c] & 0x7FFFu;
         gt += ((int)key > T) & (key <= 0x7C00u);
       }
@@ -359,13 +366,13 @@ struct RowPrologue {
     unsigned pos = excl_scan(gt, sm, &tot);
     if (gt != 0) {
       for (int v = v0; v < v1; ++v) {
-        const u16x8 b = xb[v];
+        const rp_u16 b = xb[v];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < RP_EV; ++c) {
           const unsigned bits = b[c];
           const unsigned key = bits & 0x7FFFu;
           if (((int)key > T) & (key <= 0x7C00u)) {
-            list[pos] = ((unsigned)((vs0 + v) * 8 + c) << 16) | bits;
+            list[pos] = ((unsigned)((vs0 + v) * RP_EV + c) << 16) | bits;
             ++pos;
           }
         }
@@ -380,10 +387,10 @@ struct RowPrologue {
   static __device__ __forceinline__ int threshold_range_of_full(const af_row_src& r,
                                                                 const unsigned short* xs, Smem& sm,
                                                                 unsigned* list, int S, int s) {
-    const int nvec = r.n >> 3;
+    const int nvec = r.n / RP_EV;
     const int V = (nvec + S - 1) / S;
     const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec);
-    return range_list(r, xs + (size_t)vs0 * 8, sm, list, vs0, vs1 - vs0);
+    return range_list(r, xs + (size_t)vs0 * RP_EV, sm, list, vs0, vs1 - vs0);
   }
 
   // The `top` largest of E logits (ties to the lower expert, slot 0 the largest) and the
@@ -445,18 +452,17 @@ struct RowPrologue {
   // (index << 16 | fp16 bits).  Returns the number of entries kept by this workgroup;
   // *nidx_total is the size of the whole index set.  `hist` is RP_SCRATCH_WORDS words of LDS.
   // `list` may be null (only idx_out / count_out are wanted).
-  // Every thread owns a contiguous run of 8-element vectors, read from LDS 16 bytes at a
+  // Every thread owns a contiguous run of RP_EV-element vectors, read from LDS one vector at a
   // time in each pass; the thread order is therefore the index order.
   static __device__ __forceinline__ int select_split(const af_row_src& r, const unsigned short* xs,
                                                      unsigned* hist, Smem& sm, unsigned* list,
                                                      int S, int s, bool store_idx, bool store_count,
                                                      int* nidx_total, bool digit1_counted = false) {
-    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
     const int tid = threadIdx.x, lane = tid & 63;
-    const int nvec = r.n >> 3;
+    const int nvec = r.n / RP_EV;
     const int cv = (nvec + THREADS - 1) / THREADS;  // vectors per thread
     const int v0 = min(tid * cv, nvec), v1 = min(v0 + cv, nvec);
-    const u16x8* xv = reinterpret_cast<const u16x8*>(xs);
+    const rp_u16* xv = reinterpret_cast<const rp_u16*>(xs);
     const int rep = lane & (RP_HIST_COPIES - 1);
     // Both selection rules become integer tests on the magnitude key:
     //   kept outright  <=>  (int)key > T  and  key <= kmax
@@ -476,9 +482,9 @@ struct RowPrologue {
         zero_hist(hist);
         __syncthreads();
         for (int v = v0; v < v1; ++v) {
-          const u16x8 b = xv[v];
+          const rp_u16 b = xv[v];
 #pragma unroll
-          for (int c = 0; c < 8; ++c)
+          for (int c = 0; c < RP_EV; ++c)
             atomicAdd(&hist[H1 + rep * 256 + ((b[c] & 0x7FFFu) >> 7)], 1u);
         }
         __syncthreads();
@@ -486,9 +492,9 @@ struct RowPrologue {
       find_digit(hist + H1, sm, 256, (unsigned)r.k);
       const unsigned d1 = sm.digit, above1 = sm.above;
       for (int v = v0; v < v1; ++v) {
-        const u16x8 b = xv[v];
+        const rp_u16 b = xv[v];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < RP_EV; ++c) {
           const unsigned key = b[c] & 0x7FFFu;
           if ((key >> 7) == d1) atomicAdd(&hist[H2 + rep * 128 + (key & 127u)], 1u);
         }
@@ -500,9 +506,9 @@ struct RowPrologue {
     }
     unsigned gt = 0, eq = 0;
     for (int v = v0; v < v1; ++v) {
-      const u16x8 b = xv[v];
+      const rp_u16 b = xv[v];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < RP_EV; ++c) {
         const unsigned key = b[c] & 0x7FFFu;
         gt += ((int)key > T) & (key <= kmax);
         eq += (int)key == T;
@@ -521,16 +527,16 @@ struct RowPrologue {
     if ((int)(pos + my_kept) > r0 && (int)pos < r1) {
       const bool to_mem = store_idx && r.idx_out != nullptr;
       for (int v = v0; v < v1; ++v) {
-        const u16x8 b = xv[v];
+        const rp_u16 b = xv[v];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < RP_EV; ++c) {
           const unsigned bits = b[c];
           const unsigned key = bits & 0x7FFFu;
           const bool is_eq = (int)key == T;
           const bool keep = (((int)key > T) & (key <= kmax)) | (is_eq & (eq_seen < quota));
           eq_seen += is_eq;
           if (keep & ((int)pos >= r0) & ((int)pos < r1)) {
-            const int j = v * 8 + c;
+            const int j = v * RP_EV + c;
             if (list != nullptr) list[pos - r0] = ((unsigned)j << 16) | bits;
             if (to_mem) r.idx_out[pos] = j;
           }
