@@ -197,8 +197,16 @@ __device__ __forceinline__ void af_stores_done() {
 __device__ __forceinline__ void af_ticket_reset(int* t) {
   __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// -DAF_TICKET_ACQ_REL builds the form that is ordered by the language's memory model alone
+// (the release writes the XCD's L2 back, the acquire invalidates it).  Measured: about 2 us
+// more per kernel (7B stack 2.49 -> 2.76 ms per token), so the default relies on the
+// write-through / acknowledged-store behaviour described above.
 __device__ __forceinline__ int af_ticket_take(int* t) {
+#ifdef AF_TICKET_ACQ_REL
+  return __hip_atomic_fetch_add(t, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+#else
   return __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
 }
 #endif
 
