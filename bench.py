@@ -372,6 +372,8 @@ def main() -> int:
                     help="also run three plain 256 MiB device copies (float4 per lane), the known-size "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-threshold-leg", action="store_true",
+                    help="skip the second measurement (threshold form of the selection) of a top-k run")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--layer-kernel", action="store_true",
                     help="one launch per layer (AF_OPT_LAYER_KERNEL) instead of one per operator")
@@ -439,10 +441,11 @@ def main() -> int:
 
     sel = M.select_cfg(B.AF_SEL_TOPK, ks)
     keep_frac = None
-    if args.select == "threshold":
+    def threshold_selection():
         # Calibration (untimed): decode --calib-tokens synthetic tokens layer by layer with
         # top-k selection at the target sparsity, pooling the magnitudes of every operator's
         # input; the thresholds of one operator come from its pooled histogram.
+        sel_k = M.select_cfg(B.AF_SEL_TOPK, ks)
         hists = [[ctx.calib_hist() for _ in range(4)] for _ in range(L)]
         torch.cuda.synchronize()
         scales = S.channel_scales(0, shape.d_model, shape.name)
@@ -451,7 +454,7 @@ def main() -> int:
             cur = torch.from_numpy(S.activation(0, scales, "hidden", tok)).cuda()
             torch.cuda.synchronize()
             for l in range(L):
-                st.layer(l, cur, bufs[l & 1], kv_len, kv_len, sel)
+                st.layer(l, cur, bufs[l & 1], kv_len, kv_len, sel_k)
                 ctx.calib_accumulate_layer(st.cfg, hists[l])
                 cur = bufs[l & 1]
             ctx.synchronize()
@@ -463,9 +466,24 @@ def main() -> int:
         st.run(hin, kv_len, kv_len, sel_sets, group=args.group, reuse_points=args.reuse_points)
         ctx.synchronize()
         src_of = lambda l, p: l - l % args.group if (args.group > 1 and args.reuse_points >> p & 1) else l
-        kept = [[int(st.sets[src_of(l, p)].count[p].item()) for p in range(4)] for l in range(L)]
-        keep_frac = [round(sum(kept[l][p] for l in range(L)) / (L * widths[p]), 4) for p in range(4)]
-        sel = [M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l], flags=B.AF_SEL_SKIP_SETS) for l in range(L)]
+        kept_ = [[int(st.sets[src_of(l, p)].count[p].item()) for p in range(4)] for l in range(L)]
+        keep_frac_ = [round(sum(kept_[l][p] for l in range(L)) / (L * widths[p]), 4) for p in range(4)]
+        sel_ = [M.select_cfg(B.AF_SEL_THRESHOLD, t=thr[l], flags=B.AF_SEL_SKIP_SETS) for l in range(L)]
+        return sel_, keep_frac_, kept_, thr
+
+    def weight_bytes(rows_):
+        """Active weight bytes of one token (the four operators of every layer)."""
+        bpw_ = 2.0 if kind == B.AF_W_F16 else 0.5
+        outs_ = (shape.qkv_out, shape.d_model, 2 * shape.d_ffn, shape.d_model)
+        ab = sum(rows_[l][p] * outs_[p] for l in range(L) for p in range(4)) * bpw_
+        if kind == B.AF_W_Q4G32:   # every scale row is touched at these sparsities
+            ab += L * sum(widths[p] // 32 * outs_[p] for p in range(4)) * 2
+        elif kind == B.AF_W_Q4CL:  # a channel's scales travel with its nibbles
+            ab += sum(rows_[l][p] * (outs_[p] // 32) * 2 for l in range(L) for p in range(4))
+        return ab
+
+    if args.select == "threshold":
+        sel, keep_frac, kept, thr = threshold_selection()
     run = lambda: st.run(hin, kv_len, kv_len, sel, group=args.group, reuse_points=args.reuse_points)
     run()
     ctx.synchronize()
@@ -505,15 +523,8 @@ def main() -> int:
                "min": round(per_step[0], 4), "max": round(per_step[-1], 4),
                "note": "event pair per step; the events add a little to each step"}
 
-    # active weight bytes of one token (the four operators of every layer)
-    bpw = 2.0 if kind == B.AF_W_F16 else 0.5
-    outs = (shape.qkv_out, shape.d_model, 2 * shape.d_ffn, shape.d_model)
     rows = [list(ks)] * L if keep_frac is None else kept     # active channels per layer and point
-    active_bytes = sum(rows[l][p] * outs[p] for l in range(L) for p in range(4)) * bpw
-    if kind == B.AF_W_Q4G32:   # every scale row is touched at these sparsities
-        active_bytes += L * sum(widths[p] // 32 * outs[p] for p in range(4)) * 2
-    elif kind == B.AF_W_Q4CL:  # a channel's scales travel with its nibbles
-        active_bytes += sum(rows[l][p] * (outs[p] // 32) * 2 for l in range(L) for p in range(4))
+    active_bytes = weight_bytes(rows)
 
     # ---- every operator of the step, in place: device time stamps written by the kernels ---
     per_op = None
@@ -696,6 +707,39 @@ def main() -> int:
     roofline["measured_stream_read_shape"] = best_shape
     roofline["measured_stream_read_GBps"] = round(stream_gbps, 1)
     roofline["frac_of_measured_stream_read"] = round(achieved / stream_gbps, 4)
+
+    # ---- the same stack with the threshold form of the selection (Section 6: thresholds
+    # preloaded per operator), reported beside the top-k headline -------------------------
+    thr_form = None
+    if args.select == "topk" and not args.no_threshold_leg and graph is not None and args.group == 1:
+        sel_t, kf_t, kept_t, _ = threshold_selection()
+        run_t = lambda: st.run(hin, kv_len, kv_len, sel_t)
+        run_t()
+        ctx.synchronize()
+        ctx.capture_begin()
+        run_t()
+        g_t = ctx.capture_end()
+        for _ in range(args.warmup):
+            ctx.graph_launch(g_t)
+        ctx.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ctx.graph_launch(g_t)
+        ctx.synchronize()
+        torch.cuda.synchronize()
+        dt_t = time.perf_counter() - t0
+        ctx.graph_destroy(g_t)
+        ab_t = weight_bytes(kept_t)
+        thr_form = {"value": round(args.steps / dt_t, 2), "unit": "tokens/s",
+                    "ms_per_step": round(dt_t / args.steps * 1e3, 4),
+                    "kept_fraction_by_point": kf_t, "calib_tokens": args.calib_tokens,
+                    "active_weight_bytes_per_token": int(ab_t),
+                    "active_weight_GBps": round(ab_t / (dt_t / args.steps) / 1e9, 1),
+                    "active_weight_frac_of_hbm_peak": round(ab_t / (dt_t / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "note": "same stack, same token; per-operator thresholds calibrated for the target "
+                            "sparsity, compared inside the GEMV launches (no index lists); "
+                            "bench.py --select threshold makes this the timed configuration"}
 
     # ---- CPU oracle on a bounded sample ------------------------------------------------
     cpu = None
@@ -880,6 +924,8 @@ def main() -> int:
                               "the KV rows it reads); fractions use us_to_next_start")
     if keep_frac is not None:
         out["config"]["kept_fraction_by_point"] = keep_frac
+    if thr_form is not None:
+        out["threshold_form"] = thr_form
     if lfu is not None:
         out["lfu_cache"] = lfu
     if overlap is not None:
