@@ -120,6 +120,95 @@ def union_bench(args, S, B, torch, np) -> int:
     return 0
 
 
+def batch_layer_bench(args, S, B, M, torch, np) -> int:
+    """--batch-layer B: one whole decoder layer of --shape for B tokens decoded together
+    (af_decode_layer_batch): per-token selection, union GEMVs, per-token attention; each token has
+    its own KV cache and length."""
+    shape = S.MODEL_SHAPES[args.shape]
+    Bt, sp = args.batch_layer, args.sparsity
+    widths = (shape.d_model, shape.n_heads * shape.head_dim, shape.d_model, shape.d_ffn)
+    outs = (shape.qkv_out, shape.d_model, 2 * shape.d_ffn, shape.d_model)
+    ks = tuple(keep_count(n, sp) for n in widths)
+    kv_cap = args.kv_len + 16
+    ctx = B.Context(0)
+    w = S.device_layer_weights(0, shape, 0)
+    lay = M.DeviceLayer(ctx, shape, w)
+    del w
+    cfg = M.layer_cfg(shape)
+    sc = S.channel_scales(0, shape.d_model, shape.name)          # shared by the tokens of the batch
+    H = torch.from_numpy(np.stack([S.activation(0, sc, "hidden", b) for b in range(Bt)])).cuda()
+    Hout = torch.zeros_like(H)
+    kv_lens = [max(1, args.kv_len - 37 * b) for b in range(Bt)]   # every token at its own length
+    caches = [S.device_kv_cache(0, shape, b, kv_cap, kv_lens[b]) for b in range(Bt)]
+    Ks, Vs = [c[0] for c in caches], [c[1] for c in caches]
+    idx = [torch.zeros((Bt, n), dtype=torch.int32, device="cuda") for n in widths]
+    cnt = [torch.zeros(Bt, dtype=torch.int32, device="cuda") for _ in widths]
+    sets = B.IdxSets()
+    for p in range(4):
+        sets.idx[p] = idx[p].data_ptr()
+        sets.count[p] = cnt[p].data_ptr()
+    un = torch.zeros(4, dtype=torch.int32, device="cuda")
+    sel = M.select_cfg(B.AF_SEL_TOPK, ks)
+    torch.cuda.synchronize()
+    run = lambda: ctx.decode_layer_batch(cfg, lay.struct(), H, Hout, Ks, Vs, kv_lens, kv_cap, kv_lens, sel, sets, un)
+    run()
+    ctx.synchronize()
+    union_rows = [int(v) for v in un.cpu().numpy()]
+    ctx.capture_begin()
+    run()
+    graph = ctx.capture_end()
+    for _ in range(args.warmup):
+        ctx.graph_launch(graph)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.graph_launch(graph)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.graph_destroy(graph)
+    # the same tokens one after the other through the single-token layer, for comparison
+    one = M.DeviceStack(ctx, shape, [lay], [(Ks[0], Vs[0])], kv_cap)
+    h1 = H[0].contiguous()
+    one.layer(0, h1, one.hidden_out, kv_lens[0], kv_lens[0], sel)
+    ctx.synchronize()
+    ctx.capture_begin()
+    one.layer(0, h1, one.hidden_out, kv_lens[0], kv_lens[0], sel)
+    g1 = ctx.capture_end()
+    for _ in range(5):
+        ctx.graph_launch(g1)
+    ctx.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.graph_launch(g1)
+    ctx.synchronize()
+    dt1 = time.perf_counter() - t0
+    ctx.graph_destroy(g1)
+    union_bytes = sum(r * o * 2 for r, o in zip(union_rows, outs))
+    ms = dt / args.steps * 1e3
+    out = {
+        "metric": "active-weight GB/s (% of HBM peak) + decode tokens/s, 7B-shape @50% sparsity",
+        "value": round(Bt * args.steps / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{args.shape}-shape decoder layer, B={Bt} tokens decoded together "
+                               f"(af_decode_layer_batch: per-token top-k at {sp}% sparsity, union GEMVs, "
+                               f"per-token attention over own KV caches of {kv_lens} tokens)",
+                   "B": Bt, "k": list(ks), "graph": True,
+                   "union_fraction_of_channels": [round(r / n, 4) for r, n in zip(union_rows, widths)]},
+        "union_weight_bytes_per_step": union_bytes,
+        "union_weight_GBps": round(union_bytes / (ms * 1e-3) / 1e9, 1),
+        "union_weight_frac_of_hbm_peak": round(union_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "single_token_layer_ms": round(dt1 / args.steps * 1e3, 4),
+        "speedup_over_token_by_token": round(Bt * dt1 / dt, 2),
+        "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
 def config0_bench(args, S, B, torch, np) -> int:
     """--config0: one 2048x2048 fp16 layer, top-k 50 % (k = 1024), selection fused into the GEMV.
     4 MB of active weights fit every cache, so the launch is timed cold (rotating through 160
@@ -366,6 +455,8 @@ def main() -> int:
                     help="with --group > 1: report the overlap of the reused sets with each layer's own selection")
     ap.add_argument("--union", type=int, default=0, metavar="B",
                     help="small-batch union GEMV over the four operators of one layer of --shape (e.g. 70b) with B tokens")
+    ap.add_argument("--batch-layer", type=int, default=0, metavar="B",
+                    help="one whole decoder layer of --shape for B tokens decoded together (af_decode_layer_batch)")
     ap.add_argument("--config0", action="store_true",
                     help="the single 2048x2048 layer of BASELINE config 0, cold and warm")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -398,6 +489,8 @@ def main() -> int:
         return config0_bench(args, S, B, torch, np)
     if args.union:
         return union_bench(args, S, B, torch, np)
+    if args.batch_layer:
+        return batch_layer_bench(args, S, B, M, torch, np)
     if S.MODEL_SHAPES[args.shape].n_experts:
         return moe_bench(args, S, B, M, torch, np)
     if args.overlap and args.select != "topk":

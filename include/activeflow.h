@@ -283,6 +283,25 @@ int af_decode_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights
                     int kv_len, int kv_cap, int pos, const af_select_cfg* sel,
                     af_idx_sets* sets);
 
+/* The same layer for a small batch of B <= AF_MAX_BATCH tokens that are decoded together, each
+ * with its own KV cache, length and position (small-batch extension of the layer above; the
+ * paper decodes one token at a time, Section 2.1).  Every token selects its own active channels
+ * at the four points; each linear operator then reads the union of the tokens' sets once
+ * (af_sparse_gemv_union_f16) with every token's own mask applied, so token b's result is what
+ * af_decode_layer gives for token b alone (up to the order of the fp32 sums).
+ * hidden_in / hidden_out: fp16 [B][d_model], device (may be the same buffer).  k_caches,
+ * v_caches: HOST arrays of B device pointers, each a cache [n_kv_heads][kv_cap][head_dim] of its
+ * own; kv_len, pos: HOST arrays of B ints (kv_len[b] < kv_cap).  sel: one configuration for all
+ * tokens, AF_SEL_TOPK or AF_SEL_THRESHOLD, reuse_mask 0.  sets (required): idx[p] int32
+ * [B][n_p] (row b = token b's ascending list, n_p = input width of point p), count[p] int32 [B];
+ * both are written.  union_n: device int32 [4] that receives the size of the union at each point,
+ * or NULL.  fp16 weights only (AF_EINVAL for the 4-bit kinds).  Needs a workspace set for
+ * max_batch >= B; afterwards af_layer_tap(which) points at the [B][width] tensor of all tokens. */
+int af_decode_layer_batch(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weights* w, int B,
+                          const void* hidden_in, void* hidden_out, void* const* k_caches,
+                          void* const* v_caches, const int* kv_len, int kv_cap, const int* pos,
+                          const af_select_cfg* sel, af_idx_sets* sets, int32_t* union_n);
+
 /* n_layers layers in sequence.  w, k_caches, v_caches, sets: host arrays of n_layers
  * entries.  With group > 1, layer l with l % group != 0 reuses the sets of its group's
  * first layer at the points named by reuse_points (Section 3, N = 4); sets[l] of a

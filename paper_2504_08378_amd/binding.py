@@ -38,7 +38,7 @@ EXPORTS = [
     "af_lfu_create", "af_lfu_destroy", "af_lfu_step", "af_lfu_stats", "af_lfu_cached",
     "af_cost_eval", "af_plan_search", "af_sparse_gemv_f16_noalloc",
     "af_profile_set", "af_wall_clock_khz", "af_set_option", "af_last_device_error",
-    "af_unpack_q4_g32", "af_probe_stream_read_variant",
+    "af_unpack_q4_g32", "af_probe_stream_read_variant", "af_decode_layer_batch",
 ]
 AF_MOE_MAX_EXPERTS, AF_MOE_MAX_TOP = 16, 4
 
@@ -147,6 +147,9 @@ def lib() -> C.CDLL:
         "af_decode_stack": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), i, vp, vp,
                                 C.POINTER(vp), C.POINTER(vp), i, i, i, C.POINTER(SelectCfg), i, i, u,
                                 C.POINTER(IdxSets)]),
+        "af_decode_layer_batch": (i, [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeights), i, vp, vp,
+                                      C.POINTER(vp), C.POINTER(vp), C.POINTER(i), i, C.POINTER(i),
+                                      C.POINTER(SelectCfg), C.POINTER(IdxSets), vp]),
         "af_layer_tap": (i, [vp, i, C.POINTER(vp)]),
         "af_capture_begin": (i, [vp]),
         "af_capture_end": (i, [vp, C.POINTER(vp)]),
@@ -427,6 +430,21 @@ class Context:
             _ptr(hidden_out, torch.float16, "hidden_out"), _ptr(k_cache, torch.float16, "k_cache"),
             _ptr(v_cache, torch.float16, "v_cache"), kv_len, kv_cap, pos, C.byref(sel),
             C.byref(sets) if sets is not None else None), "af_decode_layer")
+
+    def decode_layer_batch(self, cfg: LayerCfg, w: LayerWeights, hidden_in, hidden_out, k_caches,
+                           v_caches, kv_len, kv_cap: int, pos, sel: SelectCfg, sets: IdxSets,
+                           union_n=None):
+        """B tokens at once: hidden_in / hidden_out fp16 [B][d]; k_caches, v_caches: sequences of B
+        cache tensors; kv_len, pos: sequences of B ints; sets: idx[p] int32 [B][n_p], count[p] [B]."""
+        Bt = int(hidden_in.shape[0])
+        kp = (C.c_void_p * Bt)(*[_ptr(t, torch.float16, "k_cache").value for t in k_caches])
+        vp_ = (C.c_void_p * Bt)(*[_ptr(t, torch.float16, "v_cache").value for t in v_caches])
+        kl = (C.c_int * Bt)(*[int(v) for v in kv_len])
+        ps = (C.c_int * Bt)(*[int(v) for v in pos])
+        _check(lib().af_decode_layer_batch(
+            self._h, C.byref(cfg), C.byref(w), Bt, _ptr(hidden_in, torch.float16, "hidden_in"),
+            _ptr(hidden_out, torch.float16, "hidden_out"), kp, vp_, kl, kv_cap, ps, C.byref(sel),
+            C.byref(sets), _ptr(union_n, torch.int32, "union_n")), "af_decode_layer_batch")
 
     def decode_stack(self, cfg: LayerCfg, w_array, n_layers: int, hidden_in, hidden_out,
                      k_ptrs, v_ptrs, kv_len: int, kv_cap: int, pos: int, sel,

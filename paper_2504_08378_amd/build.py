@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libactiveflow.so")
-SOURCES = ["api.hip", "select.hip", "gemv_f16.hip", "gemv_q4.hip", "union.hip", "layer.hip", "calib.hip", "planner.hip"]
+SOURCES = ["api.hip", "select.hip", "gemv_f16.hip", "gemv_q4.hip", "union.hip", "layer.hip", "batch_layer.hip", "calib.hip", "planner.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

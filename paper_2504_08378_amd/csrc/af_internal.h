@@ -17,8 +17,10 @@ struct af_ws_layout {
   size_t tickets;       // int32[AF_N_TICKETS], zero between kernels
   size_t partials;      // float[partial_floats]: split partial sums of the GEMVs
   size_t attn_part;     // float[attn_floats]: per-(head, key split) softmax partials
-  size_t act[7];        // fp16 inter-operator tensors of a layer (see af_layer_tap)
+  size_t act[7];        // fp16 inter-operator tensors of a layer, [max_batch] rows each (see af_layer_tap)
   size_t union_x;       // fp16 [max_in][8]: masked, transposed token values of the union GEMV
+  size_t union_idx;     // int32 [max_in]: union of the tokens' sets (af_decode_layer_batch)
+  size_t union_n;       // int32 [4]: its size per selection point
   size_t total;
   size_t partial_floats;
   size_t attn_floats;
@@ -153,6 +155,27 @@ int af_launch_gemv_f16(af_ctx* ctx, const af_gemv_args& a);
 // AF_OPT_VALIDATE: queue the check of a caller's index list (ascending, unique, inside [0, n))
 int af_validate_idx(af_ctx* ctx, const int32_t* idx, int nidx_host, const int32_t* nidx_dev, int n);
 int af_launch_gemv_q4(af_ctx* ctx, const af_gemv_args& a);
+
+// Union GEMV over B tokens (union.hip): builds the union of the tokens' index lists and runs
+// the gathered GEMV once for all of them.  Arguments are taken as checked by the caller.
+struct af_union_args {
+  const void* Wt;
+  int in, out, ld;
+  const half_t* X;          // [B][in]
+  int B;
+  const int32_t* idx_b;     // [B][idx_stride]
+  int idx_stride, k;        // k entries per list, or counts[b] <= k of them
+  const int32_t* counts;    // device int32[B] or null
+  int32_t* union_idx;       // [in]
+  int32_t* union_n;         // [1]
+  void* Y;                  // [B][out]
+  int y_kind;
+  const half_t* residual;   // [B][out] or null
+};
+int af_launch_union_f16(af_ctx* ctx, const af_union_args& u);
+// Rotary embedding, KV append and attention of one token (layer.hip).
+int af_launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc, void* vc,
+                        int kv_len, int kv_cap, int pos, half_t* out);
 
 // ---- cross-workgroup hand-off without cache-wide fences ------------------------------------
 // Partial results travel between workgroups (possibly on different XCDs, each with its own

@@ -19,10 +19,14 @@ af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
   const size_t act_halves = (size_t)(max_in > max_out ? max_in : max_out);
   for (int i = 0; i < 7; ++i) {
     L.act[i] = off;
-    off = af_align(off + act_halves * sizeof(half_t));
+    off = af_align(off + act_halves * sizeof(half_t) * (size_t)max_batch);
   }
   L.union_x = off;
   off = af_align(off + (size_t)max_in * 8 * sizeof(half_t));
+  L.union_idx = off;
+  off = af_align(off + (size_t)max_in * sizeof(int32_t));
+  L.union_n = off;
+  off = af_align(off + 4 * sizeof(int32_t));
   L.total = off;
   return L;
 }

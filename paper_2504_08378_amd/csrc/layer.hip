@@ -258,8 +258,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   af_prof_end(p.prof);
 }
 
-static int launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc,
-                            void* vc, int kv_len, int kv_cap, int pos, half_t* out) {
+int af_launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc, void* vc,
+                        int kv_len, int kv_cap, int pos, half_t* out) {
   int KS = (kv_len + 63) / 64;
   if (KS < 1) KS = 1;
   if (KS > 64) KS = 64;
@@ -862,7 +862,7 @@ static int run_layer(af_ctx* ctx, const af_layer_cfg* cfg, const af_layer_weight
   }
   auto gemv = [&](const af_gemv_args& a) { return q4 ? af_launch_gemv_q4(ctx, a) : af_launch_gemv_f16(ctx, a); };
   if ((rc = gemv(ga[0]))) return rc;
-  if ((rc = launch_attention(ctx, cfg, qkv, kc, vc, kv_len, kv_cap, pos, attn))) return rc;
+  if ((rc = af_launch_attention(ctx, cfg, qkv, kc, vc, kv_len, kv_cap, pos, attn))) return rc;
   if ((rc = gemv(ga[1]))) return rc;
   if ((rc = gemv(ga[2]))) return rc;
   if ((rc = gemv(ga[3]))) return rc;
@@ -1123,7 +1123,7 @@ extern "C" int af_decode_moe_layer(af_ctx* ctx, const af_moe_cfg* mcfg, const af
     a.W = w->Wqkv; a.scales = (const half_t*)w->Sqkv; a.in = d; a.out = qkv_out; a.ld = qkv_out; a.y = qkv;
     if ((rc = gemv(0, 0, a, AF_PRO_RMSNORM, h_in, (const half_t*)w->g_attn_norm, x0))) return rc;
   }
-  if ((rc = launch_attention(ctx, cfg, qkv, k_cache, v_cache, kv_len, kv_cap, pos, attn))) return rc;
+  if ((rc = af_launch_attention(ctx, cfg, qkv, k_cache, v_cache, kv_len, kv_cap, pos, attn))) return rc;
   {
     af_gemv_args a{};
     a.W = w->Wo; a.scales = (const half_t*)w->So; a.in = qdim; a.out = d; a.ld = d; a.y = hmid; a.residual = h_in;

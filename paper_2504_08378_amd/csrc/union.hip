@@ -15,11 +15,12 @@
 
 struct UnionBuildParams {
   const half_t* X;         // [B][in]
-  const int32_t* idx_b;    // [B][k]
+  const int32_t* idx_b;    // [B][idx_stride], k entries used (or counts[b] of them)
+  const int32_t* counts;   // per-token list lengths on the device, or null: k for every token
   int32_t* union_idx;      // [in]
   int32_t* union_n;        // [1]
   half_t* Xm;              // [in][8]
-  int B, k, in;
+  int B, k, in, idx_stride;
   int* tickets;            // the device error word lies behind them
 };
 
@@ -29,14 +30,16 @@ __global__ __launch_bounds__(UB_THREADS) void union_build_kernel(UnionBuildParam
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int j = tid; j < p.in; j += UB_THREADS) s_mask[j] = 0;
   __syncthreads();
-  for (int b = 0; b < p.B; ++b)
-    for (int t = tid; t < p.k; t += UB_THREADS) {
-      const int j = p.idx_b[(size_t)b * p.k + t];
+  for (int b = 0; b < p.B; ++b) {
+    const int kb = p.counts ? min(max(p.counts[b], 0), p.k) : p.k;
+    for (int t = tid; t < kb; t += UB_THREADS) {
+      const int j = p.idx_b[(size_t)b * p.idx_stride + t];
       if ((unsigned)j < (unsigned)p.in)
         atomicOr(&s_mask[j], 1u << b);
       else  // broken precondition: the entry is dropped and reported
         af_report_bad_index(p.tickets);
     }
+  }
   __syncthreads();
   // masked, transposed token values
   for (int j = tid; j < p.in; j += UB_THREADS) {
@@ -85,6 +88,7 @@ struct UnionGemvParams {
   float* partials;         // [S][B][out_pad]
   int* tickets;
   void* Y;                 // [B][out]
+  const half_t* residual;  // [B][out] added to the product, or null
   int out, ld, nidx_host, y_kind, out_pad, B;
 };
 
@@ -185,6 +189,7 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
   const int tile0 = blockIdx.x * TW;
   auto store = [&](int b, int colg, float v) {
     if (b < p.B && colg < p.out) {
+      if (p.residual) v += (float)p.residual[(size_t)b * p.out + colg];
       if (p.y_kind == AF_F16)
         reinterpret_cast<half_t*>(p.Y)[(size_t)b * p.out + colg] = (half_t)v;
       else
@@ -225,32 +230,20 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
   if (tid == 0) af_ticket_reset(&p.tickets[blockIdx.x]);
 }
 
-extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
-                                        const void* X_f16, int B, const int32_t* idx_b, int k,
-                                        int32_t* union_idx, int32_t* union_n, void* Y, int y_kind) {
-  if (!ctx || !Wt || !X_f16 || !union_idx || !union_n || !Y || (!idx_b && k > 0)) return AF_ENULL;
-  if (in <= 0 || out <= 0 || in > AF_MAX_N || B < 1 || B > AF_MAX_BATCH || k < 0 || k > in)
-    return AF_EINVAL;
-  if (out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
-  if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
-  if (!ctx->ws) return AF_EWORKSPACE;
-  if (in > ctx->max_in || out > ctx->max_out || B > ctx->max_batch) return AF_EWORKSPACE;
-
+int af_launch_union_f16(af_ctx* ctx, const af_union_args& u) {
+  const int in = u.in, out = u.out, B = u.B, k = u.k;
   UnionBuildParams bp;
-  bp.X = (const half_t*)X_f16;
-  bp.idx_b = idx_b;
-  bp.union_idx = union_idx;
-  bp.union_n = union_n;
+  bp.X = u.X;
+  bp.idx_b = u.idx_b;
+  bp.counts = u.counts;
+  bp.union_idx = u.union_idx;
+  bp.union_n = u.union_n;
   bp.Xm = (half_t*)(ctx->ws + ctx->lay.union_x);
   bp.B = B;
   bp.k = k;
   bp.in = in;
+  bp.idx_stride = u.idx_stride;
   bp.tickets = (int*)(ctx->ws + ctx->lay.tickets);
-  if (ctx->validate)
-    for (int b = 0; b < B; ++b) {
-      const int rc = af_validate_idx(ctx, idx_b + (size_t)b * k, k, nullptr, in);
-      if (rc) return rc;
-    }
   static bool lds_attr_set = false;
   if (!lds_attr_set) {  // up to 128 KB of dynamic LDS for the channel masks
     lds_attr_set = true;
@@ -277,17 +270,18 @@ extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int
   while (S > 1 && (size_t)S * NB * out_pad > ctx->lay.partial_floats) --S;
 
   UnionGemvParams p;
-  p.W = (const half_t*)Wt;
+  p.W = (const half_t*)u.Wt;
   p.Xm = bp.Xm;
-  p.idx = union_idx;
-  p.nidx_dev = union_n;
+  p.idx = u.union_idx;
+  p.nidx_dev = u.union_n;
   p.partials = (float*)(ctx->ws + ctx->lay.partials);
   p.tickets = (int*)(ctx->ws + ctx->lay.tickets);
-  p.Y = Y;
+  p.Y = u.Y;
+  p.residual = u.residual;
   p.out = out;
-  p.ld = ld;
+  p.ld = u.ld;
   p.nidx_host = nidx_max;
-  p.y_kind = y_kind;
+  p.y_kind = u.y_kind;
   p.out_pad = out_pad;
   p.B = B;
   dim3 grid(tiles, S), block(UG_THREADS);
@@ -307,4 +301,36 @@ extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int
 #undef UNION_LAUNCH
   AF_LAUNCH_CHECK();
   return AF_OK;
+}
+
+extern "C" int af_sparse_gemv_union_f16(af_ctx* ctx, const void* Wt, int in, int out, int ld,
+                                        const void* X_f16, int B, const int32_t* idx_b, int k,
+                                        int32_t* union_idx, int32_t* union_n, void* Y, int y_kind) {
+  if (!ctx || !Wt || !X_f16 || !union_idx || !union_n || !Y || (!idx_b && k > 0)) return AF_ENULL;
+  if (in <= 0 || out <= 0 || in > AF_MAX_N || B < 1 || B > AF_MAX_BATCH || k < 0 || k > in)
+    return AF_EINVAL;
+  if (out % 8 || ld % 8 || ld < out) return AF_ESHAPE;
+  if (y_kind != AF_F16 && y_kind != AF_F32) return AF_EINVAL;
+  if (!ctx->ws) return AF_EWORKSPACE;
+  if (in > ctx->max_in || out > ctx->max_out || B > ctx->max_batch) return AF_EWORKSPACE;
+  if (ctx->validate)
+    for (int b = 0; b < B; ++b) {
+      const int rc = af_validate_idx(ctx, idx_b + (size_t)b * k, k, nullptr, in);
+      if (rc) return rc;
+    }
+  af_union_args u{};
+  u.Wt = Wt;
+  u.in = in;
+  u.out = out;
+  u.ld = ld;
+  u.X = (const half_t*)X_f16;
+  u.B = B;
+  u.idx_b = idx_b;
+  u.idx_stride = k;
+  u.k = k;
+  u.union_idx = union_idx;
+  u.union_n = union_n;
+  u.Y = Y;
+  u.y_kind = y_kind;
+  return af_launch_union_f16(ctx, u);
 }
