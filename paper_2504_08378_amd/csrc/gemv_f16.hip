@@ -79,27 +79,53 @@ static void choose_config(const af_ctx* ctx, int out, int nidx, bool selects, bo
   *s_out = S;
 }
 
-template <int LX, int NW, bool ROUTED>
+template <int LX, int NW, bool ROUTED, int MODE>
 static void launch_one(dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW, ROUTED>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_f16_kernel<LX, 8, NW, ROUTED, MODE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW, ROUTED>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_f16_kernel<LX, 8, NW, ROUTED, MODE>), grid, dim3(NW * AF_WAVE), lds, st, p);
 }
 
+// The 1024-thread launches that build or select their input come in one instantiation per
+// (producer, selection) pair of a decoder layer; anything else runs the generic kernel.
 template <int LX>
 static void launch_lx(int nw, dim3 grid, size_t lds, hipStream_t st, const GemvParams& p) {
-  if (p.router_Wr != nullptr)  // the launcher has made sure of nw == 16
-    launch_one<LX, 16, true>(grid, lds, st, p);
-  else if (nw == 16)
-    launch_one<LX, 16, false>(grid, lds, st, p);
-  else if (nw == 8)
-    launch_one<LX, 8, false>(grid, lds, st, p);
-  else
-    launch_one<LX, 4, false>(grid, lds, st, p);
+  if (p.router_Wr != nullptr) {  // the launcher has made sure of nw == 16 and of an RMSNorm producer
+    const int mode = gemv_mode_of(p);
+    if (mode == GEMV_MODE(AF_PRO_RMSNORM, 1))
+      launch_one<LX, 16, true, GEMV_MODE(AF_PRO_RMSNORM, 1)>(grid, lds, st, p);
+    else if (mode == GEMV_MODE(AF_PRO_RMSNORM, 3))
+      launch_one<LX, 16, true, GEMV_MODE(AF_PRO_RMSNORM, 3)>(grid, lds, st, p);
+    else
+      launch_one<LX, 16, true, -1>(grid, lds, st, p);
+  } else if (nw == 16) {
+    switch (gemv_mode_of(p)) {
+#define AF_MODE_CASE(pro, kind) \
+  case GEMV_MODE(pro, kind):    \
+    launch_one<LX, 16, false, GEMV_MODE(pro, kind)>(grid, lds, st, p); \
+    break;
+      AF_MODE_CASE(AF_PRO_RMSNORM, 1)
+      AF_MODE_CASE(AF_PRO_NONE, 1)
+      AF_MODE_CASE(AF_PRO_SILUMUL, 1)
+      AF_MODE_CASE(AF_PRO_RMSNORM, 3)
+      AF_MODE_CASE(AF_PRO_NONE, 3)
+      AF_MODE_CASE(AF_PRO_SILUMUL, 3)
+      AF_MODE_CASE(AF_PRO_RMSNORM, 0)
+      AF_MODE_CASE(AF_PRO_NONE, 0)
+      AF_MODE_CASE(AF_PRO_SILUMUL, 0)
+#undef AF_MODE_CASE
+      default:
+        launch_one<LX, 16, false, -1>(grid, lds, st, p);
+    }
+  } else if (nw == 8) {
+    launch_one<LX, 8, false, -1>(grid, lds, st, p);
+  } else {
+    launch_one<LX, 4, false, -1>(grid, lds, st, p);
+  }
 }
 
 int af_plan_gemv_f16(af_ctx* ctx, const af_gemv_args& a, bool whole_layer, GemvPlan* plan) {

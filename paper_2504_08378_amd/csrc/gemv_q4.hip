@@ -77,8 +77,20 @@ __device__ __forceinline__ void q4_fma8(float* acc, unsigned w, float x, float x
 
 // CL = false: scales [in/32][ld], one per (group of 32 input channels, column);
 // CL = true:  scales [in][ld/32], one per (input channel, group of 32 columns).
-template <int LX, int U, int NW, bool CL, bool ROUTED>
-__global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
+// MODE: producer and row source as compile-time constants (pro | kind << 2; kind 0 rows given,
+// 1 top-k, 2 threshold with a list, 3 threshold per channel range), or -1 for the generic kernel
+// that reads them from its arguments; see gemv_f16_body.h for what this buys.
+#define Q4_MODE(pro, kind) ((pro) | ((kind) << 2))
+template <int LX, int U, int NW, bool CL, bool ROUTED, int MODE = -1>
+__global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p_in) {
+  Q4Params p = p_in;
+  if constexpr (MODE >= 0) {
+    constexpr int pro = MODE & 3, kind = MODE >> 2;
+    p.rows.pro = pro;
+    p.rows.sel = kind == 0 ? (int)AF_ROWS_GIVEN : (kind == 1 ? (int)AF_SEL_TOPK : (int)AF_SEL_THRESHOLD);
+    p.use_lds_x = (pro != AF_PRO_NONE || kind != 0) ? 1 : 0;
+    p.range_sel = kind == 3 ? 1 : 0;
+  }
   constexpr int THREADS = NW * AF_WAVE;
   constexpr int LY = AF_WAVE / LX;
   constexpr int TW = LX * 8;
@@ -318,34 +330,58 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p) {
   af_prof_end(p.prof);
 }
 
-template <int LX, int NW, bool CL, bool ROUTED>
+template <int LX, int NW, bool CL, bool ROUTED, int MODE>
 static void q4_launch_one(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   static bool attr_done = false;
   if (!attr_done) {  // the input vector and the staged rows can need more than the default 64 KB
     attr_done = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW, CL, ROUTED>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_q4_kernel<LX, 8, NW, CL, ROUTED, MODE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, AF_GEMV_LDS_BUDGET);
   }
-  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW, CL, ROUTED>), grid, dim3(NW * AF_WAVE), lds, st, p);
+  hipLaunchKernelGGL((gemv_q4_kernel<LX, 8, NW, CL, ROUTED, MODE>), grid, dim3(NW * AF_WAVE), lds, st, p);
+}
+
+// the (producer, selection) pairs of a decoder layer get an instantiation of their own
+template <int LX, bool CL>
+static void q4_launch_mode(dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
+  const int kind = p.rows.sel == AF_ROWS_GIVEN ? 0 : (p.rows.sel == AF_SEL_TOPK ? 1 : (p.range_sel ? 3 : 2));
+  switch (Q4_MODE(p.rows.pro, kind)) {
+#define AF_MODE_CASE(pro, kind_) \
+  case Q4_MODE(pro, kind_):      \
+    q4_launch_one<LX, 16, CL, false, Q4_MODE(pro, kind_)>(grid, lds, st, p); \
+    break;
+    AF_MODE_CASE(AF_PRO_RMSNORM, 1)
+    AF_MODE_CASE(AF_PRO_NONE, 1)
+    AF_MODE_CASE(AF_PRO_SILUMUL, 1)
+    AF_MODE_CASE(AF_PRO_RMSNORM, 3)
+    AF_MODE_CASE(AF_PRO_NONE, 3)
+    AF_MODE_CASE(AF_PRO_SILUMUL, 3)
+    AF_MODE_CASE(AF_PRO_RMSNORM, 0)
+    AF_MODE_CASE(AF_PRO_NONE, 0)
+    AF_MODE_CASE(AF_PRO_SILUMUL, 0)
+#undef AF_MODE_CASE
+    default:
+      q4_launch_one<LX, 16, CL, false, -1>(grid, lds, st, p);
+  }
 }
 
 template <int LX>
 static void q4_launch_lx(int nw, bool cl, dim3 grid, size_t lds, hipStream_t st, const Q4Params& p) {
   if (p.router_Wr != nullptr) {  // the launcher has made sure of nw == 16
     if (cl)
-      q4_launch_one<LX, 16, true, true>(grid, lds, st, p);
+      q4_launch_one<LX, 16, true, true, -1>(grid, lds, st, p);
     else
-      q4_launch_one<LX, 16, false, true>(grid, lds, st, p);
+      q4_launch_one<LX, 16, false, true, -1>(grid, lds, st, p);
   } else if (nw == 16) {
     if (cl)
-      q4_launch_one<LX, 16, true, false>(grid, lds, st, p);
+      q4_launch_mode<LX, true>(grid, lds, st, p);
     else
-      q4_launch_one<LX, 16, false, false>(grid, lds, st, p);
+      q4_launch_mode<LX, false>(grid, lds, st, p);
   } else {
     if (cl)
-      q4_launch_one<LX, 4, true, false>(grid, lds, st, p);
+      q4_launch_one<LX, 4, true, false, -1>(grid, lds, st, p);
     else
-      q4_launch_one<LX, 4, false, false>(grid, lds, st, p);
+      q4_launch_one<LX, 4, false, false, -1>(grid, lds, st, p);
   }
 }
 

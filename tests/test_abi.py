@@ -54,6 +54,7 @@ def test_null_context_is_rejected_on_the_host(L):
     assert L.af_sparse_gemv_f16(null, one, 8, 8, 8, one, one, 4, null, one, 0, null) == -2
     assert L.af_sparse_gemv_q4(null, one, one, 32, 8, 8, one, one, 4, null, one, 0, null) == -2
     assert L.af_sparse_gemv_union_f16(null, one, 8, 8, 8, one, 1, one, 4, one, one, one, 0) == -2
+    assert L.af_decode_layer_batch(null, None, None, 2, one, one, None, None, None, 16, None, None, None, null) == -2
     assert L.af_set_workspace(null, one, 1 << 20, 8, 8, 1) == -2
     assert L.af_destroy(null) == -2
     assert L.af_capture_begin(null) == -2
