@@ -21,6 +21,8 @@ struct af_ws_layout {
   size_t union_x;       // fp16 [max_in][8]: masked, transposed token values of the union GEMV
   size_t union_idx;     // int32 [max_in]: union of the tokens' sets (af_decode_layer_batch)
   size_t union_n;       // int32 [4]: its size per selection point
+  size_t union_ranges;  // int32 [max_in rounded up to 256]: the union builder's per-range lists
+  size_t union_range_cnt; // int32 [AF_MAX_N / 256]
   size_t total;
   size_t partial_floats;
   size_t attn_floats;

@@ -27,6 +27,10 @@ af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
   off = af_align(off + (size_t)max_in * sizeof(int32_t));
   L.union_n = off;
   off = af_align(off + 4 * sizeof(int32_t));
+  L.union_ranges = off;
+  off = af_align(off + ((size_t)max_in + 256) * sizeof(int32_t));
+  L.union_range_cnt = off;
+  off = af_align(off + (AF_MAX_N / 256) * sizeof(int32_t));
   L.total = off;
   return L;
 }

@@ -3,77 +3,111 @@
 //
 //   Y[b][o] = sum_{j in idx_b[b]} Wt[j][o] * X[b][j]
 //
-// Step 1 (one workgroup): scatter the B index lists into a per-channel bit mask in LDS, emit
-// the ascending union U, and write Xm[j][b] = X[b][j] if token b keeps channel j else 0
-// (fp16, 8 tokens per row = one 16-byte load in the GEMV).
+// Step 1 (two launches, one workgroup per 256 channels): scatter the B index lists into a
+// per-channel bit mask in LDS, write Xm[j][b] = X[b][j] if token b keeps channel j else 0
+// (fp16, 8 tokens per row = one 16-byte load in the GEMV), and emit the ascending union U
+// (each workgroup its own range, then moved into place behind the lower ranges).
 // Step 2: the gathered GEMV of gemv_f16.hip over U with B accumulator sets per lane; every
 // weight row of the union is read once for all tokens.
 #include "af_internal.h"
 
 #define UB_THREADS 1024
 #define UB_WAVES (UB_THREADS / AF_WAVE)
+#define UB_RANGE 256   // channels per workgroup of the builder
+#define UB_MAX_RANGES (AF_MAX_N / UB_RANGE)
 
 struct UnionBuildParams {
   const half_t* X;         // [B][in]
   const int32_t* idx_b;    // [B][idx_stride], k entries used (or counts[b] of them)
   const int32_t* counts;   // per-token list lengths on the device, or null: k for every token
+  int32_t* range_list;     // [ranges][UB_RANGE]: the union's channels of each range, ascending
+  int32_t* range_cnt;      // [ranges]
   int32_t* union_idx;      // [in]
   int32_t* union_n;        // [1]
   half_t* Xm;              // [in][8]
-  int B, k, in, idx_stride;
+  int B, k, in, idx_stride, ranges;
   int* tickets;            // the device error word lies behind them
 };
 
-__global__ __launch_bounds__(UB_THREADS) void union_build_kernel(UnionBuildParams p) {
-  extern __shared__ unsigned s_mask[];  // one word per channel (bit b = token b keeps it)
-  __shared__ unsigned s_wtot[UB_WAVES];
+// Builder, first launch: workgroup r owns the channels [r * UB_RANGE, (r + 1) * UB_RANGE).  It
+// reads every token's whole list (so a list that breaks the ascending-order precondition is
+// still handled entry by entry: what lies in the range is taken, what lies outside [0, in) is
+// dropped and reported), marks its channels in a bit mask in LDS, writes their masked,
+// transposed token values and leaves its part of the union, in ascending order, in range_list.
+__global__ __launch_bounds__(UB_THREADS) void union_scan_kernel(UnionBuildParams p) {
+  __shared__ unsigned s_mask[UB_RANGE];  // bit b = token b keeps the channel
+  __shared__ unsigned s_wtot[UB_RANGE / AF_WAVE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int j = tid; j < p.in; j += UB_THREADS) s_mask[j] = 0;
+  const int r = blockIdx.x;
+  const int c0 = r * UB_RANGE, cn = min(UB_RANGE, p.in - c0);
+  if (tid < UB_RANGE) s_mask[tid] = 0;
   __syncthreads();
   for (int b = 0; b < p.B; ++b) {
     const int kb = p.counts ? min(max(p.counts[b], 0), p.k) : p.k;
-    for (int t = tid; t < kb; t += UB_THREADS) {
-      const int j = p.idx_b[(size_t)b * p.idx_stride + t];
-      if ((unsigned)j < (unsigned)p.in)
-        atomicOr(&s_mask[j], 1u << b);
-      else  // broken precondition: the entry is dropped and reported
-        af_report_bad_index(p.tickets);
+    const int32_t* list = p.idx_b + (size_t)b * p.idx_stride;
+    for (int t0 = tid; t0 < kb; t0 += 8 * UB_THREADS) {
+      int j[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) j[u] = t0 + u * UB_THREADS < kb ? list[t0 + u * UB_THREADS] : c0 - 1 - UB_RANGE;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if ((unsigned)(j[u] - c0) < (unsigned)cn)
+          atomicOr(&s_mask[j[u] - c0], 1u << b);
+        else if (r == 0 && t0 + u * UB_THREADS < kb && (unsigned)j[u] >= (unsigned)p.in)
+          af_report_bad_index(p.tickets);  // broken precondition: the entry is dropped and reported
+      }
     }
   }
   __syncthreads();
-  // masked, transposed token values
-  for (int j = tid; j < p.in; j += UB_THREADS) {
-    const unsigned m = s_mask[j];
+  // one channel per thread (the first UB_RANGE threads have one)
+  const bool in_range = tid < cn;
+  const unsigned m = in_range ? s_mask[tid] : 0u;
+  if (in_range) {
     half8 v;
 #pragma unroll
     for (int b = 0; b < 8; ++b)
-      v[b] = (b < p.B && ((m >> b) & 1u)) ? p.X[(size_t)b * p.in + j] : (half_t)0;
-    *reinterpret_cast<half8*>(p.Xm + (size_t)j * 8) = v;
+      v[b] = (b < p.B && ((m >> b) & 1u)) ? p.X[(size_t)b * p.in + c0 + tid] : (half_t)0;
+    *reinterpret_cast<half8*>(p.Xm + (size_t)(c0 + tid) * 8) = v;
   }
-  // ordered compaction: each thread owns a contiguous chunk of channels
-  const int c = (p.in + UB_THREADS - 1) / UB_THREADS;
-  const int j0 = min(tid * c, p.in), j1 = min(j0 + c, p.in);
-  unsigned cnt = 0;
-  for (int j = j0; j < j1; ++j) cnt += s_mask[j] != 0;
-  unsigned inc = cnt;
-#pragma unroll
-  for (int off = 1; off < AF_WAVE; off <<= 1) {
-    unsigned o = __shfl_up(inc, off, AF_WAVE);
-    if (lane >= off) inc += o;
-  }
-  if (lane == 63) s_wtot[wave] = inc;
+  const unsigned flag = m != 0;
+  const unsigned inc = af_wave_incl_scan(flag);
+  if (lane == 63 && wave < UB_RANGE / AF_WAVE) s_wtot[wave] = inc;
   __syncthreads();
   unsigned base = 0, total = 0;
 #pragma unroll
-  for (int w = 0; w < UB_WAVES; ++w) {
-    unsigned t = s_wtot[w];
+  for (int w = 0; w < UB_RANGE / AF_WAVE; ++w) {
+    const unsigned t = s_wtot[w];
     if (w < wave) base += t;
     total += t;
   }
-  unsigned pos = base + inc - cnt;
-  for (int j = j0; j < j1; ++j)
-    if (s_mask[j] != 0) p.union_idx[pos++] = j;
-  if (tid == 0) *p.union_n = (int)total;
+  if (flag) p.range_list[(size_t)r * UB_RANGE + base + inc - 1] = c0 + tid;
+  if (tid == 0) p.range_cnt[r] = (int)total;
+}
+
+// Builder, second launch: workgroup r moves its range's channels to their place in the union
+// (behind the channels of all lower ranges); workgroup 0 also writes the union's size.
+#define UP_THREADS 256
+__global__ __launch_bounds__(UP_THREADS) void union_place_kernel(UnionBuildParams p) {
+  __shared__ int s_base, s_total;
+  const int tid = threadIdx.x, r = blockIdx.x;
+  if (tid < AF_WAVE) {  // the first wave adds up the range counts (at most 128 of them)
+    int below = 0, all = 0;
+    for (int q = tid; q < p.ranges; q += AF_WAVE) {
+      const int c = p.range_cnt[q];
+      all += c;
+      if (q < r) below += c;
+    }
+    below = (int)af_wave_sum((unsigned)below);
+    all = (int)af_wave_sum((unsigned)all);
+    if (tid == 0) {
+      s_base = below;
+      s_total = all;
+    }
+  }
+  __syncthreads();
+  const int cnt = p.range_cnt[r];
+  if (tid < cnt) p.union_idx[s_base + tid] = p.range_list[(size_t)r * UB_RANGE + tid];
+  if (r == 0 && tid == 0) *p.union_n = s_total;
 }
 
 #define UG_THREADS 256
@@ -236,6 +270,8 @@ int af_launch_union_f16(af_ctx* ctx, const af_union_args& u) {
   bp.X = u.X;
   bp.idx_b = u.idx_b;
   bp.counts = u.counts;
+  bp.range_list = (int32_t*)(ctx->ws + ctx->lay.union_ranges);
+  bp.range_cnt = (int32_t*)(ctx->ws + ctx->lay.union_range_cnt);
   bp.union_idx = u.union_idx;
   bp.union_n = u.union_n;
   bp.Xm = (half_t*)(ctx->ws + ctx->lay.union_x);
@@ -243,16 +279,11 @@ int af_launch_union_f16(af_ctx* ctx, const af_union_args& u) {
   bp.k = k;
   bp.in = in;
   bp.idx_stride = u.idx_stride;
+  bp.ranges = (in + UB_RANGE - 1) / UB_RANGE;
   bp.tickets = (int*)(ctx->ws + ctx->lay.tickets);
-  static bool lds_attr_set = false;
-  if (!lds_attr_set) {  // up to 128 KB of dynamic LDS for the channel masks
-    lds_attr_set = true;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(union_build_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(AF_MAX_N * sizeof(unsigned)));
-  }
-  hipLaunchKernelGGL(union_build_kernel, dim3(1), dim3(UB_THREADS), (size_t)in * sizeof(unsigned),
-                     ctx->stream, bp);
+  hipLaunchKernelGGL(union_scan_kernel, dim3(bp.ranges), dim3(UB_THREADS), 0, ctx->stream, bp);
+  AF_LAUNCH_CHECK();
+  hipLaunchKernelGGL(union_place_kernel, dim3(bp.ranges), dim3(UP_THREADS), 0, ctx->stream, bp);
   AF_LAUNCH_CHECK();
 
   const int NB = B == 1 ? 1 : (B == 2 ? 2 : (B <= 4 ? 4 : 8));
