@@ -178,6 +178,10 @@ int af_launch_union_f16(af_ctx* ctx, const af_union_args& u);
 // Rotary embedding, KV append and attention of one token (layer.hip).
 int af_launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc, void* vc,
                         int kv_len, int kv_cap, int pos, half_t* out);
+// The same for B tokens in one launch; token b's qkv / out lie b * stride elements further.
+int af_launch_attention_batch(af_ctx* ctx, const af_layer_cfg* cfg, int B, const half_t* qkv,
+                              long long qkv_stride, void* const* kcs, void* const* vcs, const int* kv_len,
+                              int kv_cap, const int* pos, half_t* out, long long out_stride);
 
 // ---- cross-workgroup hand-off without cache-wide fences ------------------------------------
 // Partial results travel between workgroups (possibly on different XCDs, each with its own

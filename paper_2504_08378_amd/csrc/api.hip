@@ -13,7 +13,7 @@ af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
   L.partial_floats = (size_t)(1u << 20) + (size_t)4 * max_out * max_batch;
   L.partials = off;
   off = af_align(off + L.partial_floats * sizeof(float));
-  L.attn_floats = (size_t)(1u << 18);
+  L.attn_floats = (size_t)(1u << 18) * (size_t)max_batch;
   L.attn_part = off;
   off = af_align(off + L.attn_floats * sizeof(float));
   const size_t act_halves = (size_t)(max_in > max_out ? max_in : max_out);

@@ -8,7 +8,8 @@
 // Per selection point: one launch of B workgroups builds each token's operator input (RMSNorm,
 // copy, or SiLU(gate)*up) and selects on it (the front end of row_prologue.h, one workgroup per
 // token), one launch builds the union, one launch streams the union's weight rows for all
-// tokens.  Attention runs token by token (each token has its own cache and length).
+// tokens.  Attention is one launch over (head, key split, token); each token has its own cache,
+// length and position.
 #include <math.h>
 
 #include "af_internal.h"
@@ -145,10 +146,9 @@ extern "C" int af_decode_layer_batch(af_ctx* ctx, const af_layer_cfg* cfg, const
                                 cfg->rms_eps, d, sel, 0, x0, sets->idx[0], sets->count[0])))
     return rc;
   if ((rc = gemv(0, w->Wqkv, d, qkv_out, x0, qkv, nullptr))) return rc;
-  for (int b = 0; b < B; ++b)
-    if ((rc = af_launch_attention(ctx, cfg, qkv + (size_t)b * qkv_out, k_caches[b], v_caches[b],
-                                  kv_len[b], kv_cap, pos[b], attn + (size_t)b * qdim)))
-      return rc;
+  if ((rc = af_launch_attention_batch(ctx, cfg, B, qkv, qkv_out, k_caches, v_caches, kv_len, kv_cap, pos,
+                                      attn, qdim)))
+    return rc;
   // o + residual
   if ((rc = launch_batch_select(ctx, B, AF_PRO_NONE, attn, qdim, nullptr, 0.f, qdim, sel, 1, nullptr,
                                 sets->idx[1], sets->count[1])))

@@ -35,8 +35,12 @@ struct AttnParams {
   float cs[64], sn[64];  // cos / sin of pos * theta^(-2i/HD), i < HD/2, formed in fp64 on the host
 };
 
+// One (head, key split) workgroup of the decode attention.  cs / sn: the rotary table of the
+// token's position (kernel arguments for the single-token launch, LDS for the batched one).
 template <int HD>
-__global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) {
+__device__ __forceinline__ void attn_decode_body(const AttnParams& p, const float* cs_tab,
+                                                 const float* sn_tab, const int h, const int s,
+                                                 const int KS) {
   constexpr int LPK = HD / 8;             // lanes per key (8 dims = 16 bytes each)
   constexpr int KPB = ATT_THREADS / LPK;  // keys per workgroup iteration
   constexpr int NB = 4;                   // iterations whose loads are issued together
@@ -50,7 +54,6 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
 
   af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int h = blockIdx.x, KS = gridDim.y, s = blockIdx.y;
   const int rep = p.n_heads / p.n_kv, kvh = h / rep;
   const int T = p.kv_len;
   const int KP = (T + KS - 1) / KS;
@@ -81,14 +84,14 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
 
   if (tid < HD / 2) {
     const float a = (float)q[tid], b = (float)q[tid + HD / 2];
-    const float cs = p.cs[tid], sn = p.sn[tid];
+    const float cs = cs_tab[tid], sn = sn_tab[tid];
     const float sc = 1.0f / sqrtf((float)HD);
     s_q[tid] = (a * cs - b * sn) * sc;
     s_q[tid + HD / 2] = (b * cs + a * sn) * sc;
   } else if (owns_new && tid >= 64 && tid < 64 + HD / 2) {
     const int i = tid - 64;
     const float a = (float)kn[i], b = (float)kn[i + HD / 2];
-    const float cs = p.cs[i], sn = p.sn[i];
+    const float cs = cs_tab[i], sn = sn_tab[i];
     const half_t ha = (half_t)(a * cs - b * sn), hb = (half_t)(b * cs + a * sn);  // cache is fp16
     s_knew[i] = (float)ha;
     s_knew[i + HD / 2] = (float)hb;
@@ -258,6 +261,49 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) 
   af_prof_end(p.prof);
 }
 
+template <int HD>
+__global__ __launch_bounds__(ATT_THREADS) void attn_decode_kernel(AttnParams p) {
+  attn_decode_body<HD>(p, p.cs, p.sn, blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// The same for B tokens in one launch (af_decode_layer_batch): grid (heads, key splits, tokens);
+// every token has its own caches, length, position and number of key splits.  The rotary table
+// of a token is formed here, in fp64 like the host does for the single-token launch
+// (angle = pos * theta^(-2i/HD) with the host's theta^(-2i/HD)).
+struct AttnBatchParams {
+  AttnParams base;          // token 0's qkv / out, the shared sizes; cs / sn unused
+  half_t* k_caches[AF_MAX_BATCH];
+  half_t* v_caches[AF_MAX_BATCH];
+  int kv_lens[AF_MAX_BATCH];
+  int poss[AF_MAX_BATCH];
+  int splits[AF_MAX_BATCH];  // key splits of each token
+  double inv_freq[64];
+  long long qkv_stride, out_stride, part_stride;  // elements between the tokens
+};
+
+template <int HD>
+__global__ __launch_bounds__(ATT_THREADS) void attn_decode_batch_kernel(AttnBatchParams bp) {
+  __shared__ float s_cs[HD / 2], s_sn[HD / 2];
+  const int b = blockIdx.z;
+  const int KS = bp.splits[b];
+  if ((int)blockIdx.y >= KS) return;  // uniform for the workgroup: this token has fewer splits
+  AttnParams p = bp.base;
+  p.qkv += (size_t)b * bp.qkv_stride;
+  p.out += (size_t)b * bp.out_stride;
+  p.part += (size_t)b * bp.part_stride;
+  p.tickets += b * p.n_heads;
+  p.k_cache = bp.k_caches[b];
+  p.v_cache = bp.v_caches[b];
+  p.kv_len = bp.kv_lens[b];
+  if (threadIdx.x < HD / 2) {
+    const double ang = (double)bp.poss[b] * bp.inv_freq[threadIdx.x];
+    s_cs[threadIdx.x] = (float)cos(ang);
+    s_sn[threadIdx.x] = (float)sin(ang);
+  }
+  __syncthreads();
+  attn_decode_body<HD>(p, s_cs, s_sn, blockIdx.x, blockIdx.y, KS);
+}
+
 int af_launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv, void* kc, void* vc,
                         int kv_len, int kv_cap, int pos, half_t* out) {
   int KS = (kv_len + 63) / 64;
@@ -288,6 +334,50 @@ int af_launch_attention(af_ctx* ctx, const af_layer_cfg* cfg, const half_t* qkv,
     hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(ATT_THREADS), 0, ctx->stream, p);
   else
     hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(ATT_THREADS), 0, ctx->stream, p);
+  AF_LAUNCH_CHECK();
+  return AF_OK;
+}
+
+int af_launch_attention_batch(af_ctx* ctx, const af_layer_cfg* cfg, int B, const half_t* qkv,
+                              long long qkv_stride, void* const* kcs, void* const* vcs, const int* kv_len,
+                              int kv_cap, const int* pos, half_t* out, long long out_stride) {
+  AttnBatchParams bp{};
+  AttnParams& p = bp.base;
+  int ks_max = 1;
+  const size_t per_split = (size_t)cfg->n_heads * (cfg->head_dim + 2);
+  for (int b = 0; b < B; ++b) {
+    int KS = (kv_len[b] + 63) / 64;
+    if (KS < 1) KS = 1;
+    if (KS > 64) KS = 64;
+    while (KS > 1 && (size_t)B * KS * per_split > ctx->lay.attn_floats) --KS;
+    if ((kv_len[b] + KS - 1) / KS > ATT_MAX_KEYS) return AF_EINVAL;
+    bp.splits[b] = KS;
+    if (KS > ks_max) ks_max = KS;
+    bp.k_caches[b] = (half_t*)kcs[b];
+    bp.v_caches[b] = (half_t*)vcs[b];
+    bp.kv_lens[b] = kv_len[b];
+    bp.poss[b] = pos[b];
+  }
+  if ((size_t)B * ks_max * per_split > ctx->lay.attn_floats) return AF_EWORKSPACE;
+  p.qkv = qkv;
+  p.out = out;
+  p.part = (float*)(ctx->ws + ctx->lay.attn_part);
+  p.tickets = (int*)(ctx->ws + ctx->lay.tickets) + AF_TICKET_ATTN;
+  p.n_heads = cfg->n_heads;
+  p.n_kv = cfg->n_kv_heads;
+  p.kv_cap = kv_cap;
+  p.head_dim = cfg->head_dim;
+  p.prof = nullptr;
+  for (int i = 0; i < cfg->head_dim / 2; ++i)
+    bp.inv_freq[i] = pow((double)cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
+  bp.qkv_stride = qkv_stride;
+  bp.out_stride = out_stride;
+  bp.part_stride = (long long)ks_max * (long long)per_split;
+  dim3 grid(cfg->n_heads, ks_max, B);
+  if (cfg->head_dim == 128)
+    hipLaunchKernelGGL(attn_decode_batch_kernel<128>, grid, dim3(ATT_THREADS), 0, ctx->stream, bp);
+  else
+    hipLaunchKernelGGL(attn_decode_batch_kernel<64>, grid, dim3(ATT_THREADS), 0, ctx->stream, bp);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }
