@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # name and launch shape are repeated in the output so that a stale figure shows):
 # FETCH_SIZE KiB x fetch factor + WRITE_SIZE KiB x write factor, the factors being what the same
 # counters read for a plain 256 MiB device copy of known size.
-TRAFFIC = {("7b", "f16", 50): {"fetch_KiB": 44415.6, "fetch_factor": 2.000, "write_KiB": 409.8, "write_factor": 1.000,
-                               "kernel": "gemv_f16_kernel<64, 8, 16, false> grid 43x4",
+TRAFFIC = {("7b", "f16", 50): {"fetch_KiB": 44367.0, "fetch_factor": 2.000, "write_KiB": 409.8, "write_factor": 1.000,
+                               "kernel": "gemv_f16_kernel<64, 8, 16, false, 5> grid 43x4",
                                "source": "profiles/gateup_7b_f16_sp50_pmc_traffic.md"}}
 
 
@@ -983,7 +983,12 @@ def main() -> int:
     if args.group > 1:
         wl += f", index reuse in groups of {args.group} (points mask {args.reuse_points:#06b})"
     clocks = None
-    try:   # best effort; a child process, never an exec from this one
+    under_profiler = any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or \
+        "rocprof" in os.environ.get("LD_PRELOAD", "")
+    try:   # best effort; a child process, never an exec from this one; not under a profiler,
+        # whose preloaded library has the child start with the GPU already initialised
+        if under_profiler:
+            raise RuntimeError("skipped under a profiler")
         import subprocess
         smi = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
         clocks = {ln.split(":")[1].strip().split()[0]: ln.split("(")[-1].rstrip(")\n ")
