@@ -109,7 +109,7 @@ def union_bench(args, S, B, torch, np) -> int:
                    "B": Bt, "union_fraction_of_channels": [round(u, 4) for u in union_frac]},
         "union_weight_bytes_per_step": union_bytes,
         "union_weight_GBps": round(union_bytes * args.steps / dt / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "union_build_kernel + gemv_union_kernel (gate|up)",
+        "roofline": {"bound": "hbm", "kernel": "union_scan_kernel + union_place_kernel + gemv_union_kernel (gate|up)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "bytes_per_launch": alg, "us_per_launch": round(us, 3), "launches": 20},
