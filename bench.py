@@ -869,18 +869,19 @@ def main() -> int:
         if kind == B.AF_W_F16 and first is not None:
             mats = [np.concatenate([host_layer0["Wq"], host_layer0["Wk"], host_layer0["Wv"]]), host_layer0["Wo"],
                     np.concatenate([host_layer0["Wgate"], host_layer0["Wup"]]), host_layer0["Wdown"]]
-            mats = [m_.astype(np.float32) for m_ in mats]
+            # input-channel-major like the GPU's layout, so that an active channel is one contiguous row
+            mats = [np.ascontiguousarray(m_.astype(np.float32).T) for m_ in mats]
             xs_ = [np.asarray(v_, dtype=np.float32) for v_ in first.x]
             t_g, n_g = 0.0, 0
-            while n_g < 20 and t_g < 4.0:
+            while n_g < 40 and t_g < 4.0:
                 t1 = time.perf_counter()
                 for m_, x_, i_ in zip(mats, xs_, first.idx):
-                    _ = m_[:, i_] @ x_[i_]
+                    _ = x_[i_] @ m_[i_]
                 t_g += time.perf_counter() - t1
                 n_g += 1
             gathered = {"value": round(1.0 / (t_g / n_g * L), 3), "unit": "tokens/s",
-                        "what": "the four gathered fp32 products W[:, idx] @ x[idx] of layer 0 in NumPy "
-                                f"({n_g}x, {t_g:.1f} s), scaled to {L} layers; linear operators only"}
+                        "what": "the four gathered fp32 products x[idx] @ Wt[idx] (input-channel-major Wt) of "
+                                f"layer 0 in NumPy ({n_g}x, {t_g:.1f} s), scaled to {L} layers; linear operators only"}
             del mats
         cpu = {"value": round(cpu_tok_s, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": f"layer 0 of the stack decoded {n_done}x by the fp64 NumPy oracle "

@@ -248,6 +248,17 @@ __device__ __forceinline__ void af_report_bad_index(int* tickets) {
                         __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ceil(a / s) for 0 <= a < 2^22 and 1 <= s <= 4096 without the integer-division sequence (some
+// forty dependent instructions on this chip, in the start-up path of every workgroup): one
+// float reciprocal and a correction step.
+__device__ __forceinline__ int af_ceil_div_small(int a, int s) {
+  const int b = a + s - 1;
+  int q = (int)((float)b * __builtin_amdgcn_rcpf((float)s));
+  const int r = b - q * s;
+  q += (r >= s) - (r < 0);
+  return q;
+}
+
 // A load of data that is used once (weight rows): marked non-temporal so that it does not
 // displace lines that are used again; a plain streaming read of HBM measured about 10 % faster
 // with this mark (6.7 against 6.05 TB/s).

@@ -150,7 +150,8 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
   af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
-  const int slot = vb.bx / p.tiles_per_slot;
+  // one slot (a plain GEMV): no division
+  const int slot = p.tiles_per_slot >= vb.gx ? 0 : vb.bx / p.tiles_per_slot;
   const int tile_in = vb.bx - slot * p.tiles_per_slot;   // tile inside the slot
   const int col = tile_in * TW + lx * 8;                       // column inside the slot
   // lanes past the slot's edge read the tile's first column and are dropped at the store
@@ -164,7 +165,7 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
   int pre[PF];
   const bool prefetched = r.sel == AF_ROWS_GIVEN && r.idx != nullptr && r.nidx_dev == nullptr;
   if (prefetched) {
-    const int R = (r.nidx_host + S - 1) / S;
+    const int R = af_ceil_div_small(r.nidx_host, S);
     const int r0 = min(s * R, r.nidx_host), r1 = min(r0 + R, r.nidx_host);
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
@@ -267,7 +268,7 @@ __device__ __forceinline__ void gemv_f16_body(const GemvParams& p, const GemvPos
   } else {
     int nidx = r.nidx_host;
     if (r.nidx_dev) nidx = min(*r.nidx_dev, nidx);
-    const int R = (nidx + S - 1) / S;
+    const int R = af_ceil_div_small(nidx, S);
     const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
     const unsigned short* xg = reinterpret_cast<const unsigned short*>(r.src);
     for (int base = r0; base < r1; base += GEMV_LIST) {

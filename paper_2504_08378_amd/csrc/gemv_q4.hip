@@ -108,7 +108,8 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p_in) {
   af_prof_begin(p.prof);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lx = lane % LX, ly = lane / LX;
-  const int slot_o = blockIdx.x / p.tiles_per_slot;
+  // one slot (a plain GEMV): no division
+  const int slot_o = p.tiles_per_slot >= (int)gridDim.x ? 0 : (int)blockIdx.x / p.tiles_per_slot;
   const int tile_in = blockIdx.x - slot_o * p.tiles_per_slot;
   const int col = tile_in * TW + lx * 8;  // column inside the slot
   const int col_ld = col < p.cols_per_slot ? col : tile_in * TW;
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(NW * AF_WAVE) void gemv_q4_kernel(Q4Params p_in) {
   } else {
     int nidx = r.nidx_host;
     if (r.nidx_dev) nidx = min(*r.nidx_dev, nidx);
-    const int R = (nidx + S - 1) / S;
+    const int R = af_ceil_div_small(nidx, S);
     const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
     const unsigned short* xg = reinterpret_cast<const unsigned short*>(r.src);
     for (int base = r0; base < r1; base += Q4_LIST) {

@@ -240,7 +240,7 @@ struct RowPrologue {
                                                         bool store_x) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = r.n, nvec = n / RP_EV;
-    const int V = (nvec + S - 1) / S;
+    const int V = af_ceil_div_small(nvec, S);
     const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec), nv = vs1 - vs0;
     constexpr int B = 4;
     rp_half* xv = reinterpret_cast<rp_half*>(xs);
@@ -388,7 +388,7 @@ struct RowPrologue {
                                                                 const unsigned short* xs, Smem& sm,
                                                                 unsigned* list, int S, int s) {
     const int nvec = r.n / RP_EV;
-    const int V = (nvec + S - 1) / S;
+    const int V = af_ceil_div_small(nvec, S);
     const int vs0 = min(s * V, nvec), vs1 = min(vs0 + V, nvec);
     return range_list(r, xs + (size_t)vs0 * RP_EV, sm, list, vs0, vs1 - vs0);
   }
@@ -518,7 +518,7 @@ struct RowPrologue {
     const unsigned pre = excl_scan(gt | (eq << 16), sm, &tot);
     const int nidx = (int)((tot & 0xFFFFu) + min(tot >> 16, quota));
     *nidx_total = nidx;
-    const int R = (nidx + S - 1) / S;
+    const int R = af_ceil_div_small(nidx, S);
     const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
     unsigned pos = (pre & 0xFFFFu) + min(pre >> 16, quota);
     unsigned eq_seen = pre >> 16;

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(UG_THREADS) void gemv_union_kernel(UnionGemvParams 
   const int S = gridDim.y, s = blockIdx.y;
 
   const int nidx = min(*p.nidx_dev, p.nidx_host);
-  const int R = (nidx + S - 1) / S;
+  const int R = af_ceil_div_small(nidx, S);
   const int r0 = min(s * R, nidx), r1 = min(r0 + R, nidx);
 
   float acc[NB][8];
