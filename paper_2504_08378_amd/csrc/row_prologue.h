@@ -63,9 +63,23 @@ struct RowPrologue {
   static __device__ __forceinline__ void produce(const af_row_src& r, unsigned short* xs, Smem& sm,
                                                  bool store_x, int store_phase, int store_stride,
                                                  unsigned* hist = nullptr) {
+    // RMSNorm of a vector of at most one access per thread (n <= RP_EV * THREADS: 4096 channels
+    // for the 1024-thread kernels) takes the copy of the code without the batch of four and its
+    // masks: the front end is bound by the instructions its waves issue, and that copy issues
+    // fewer (q|k|v 15.7 -> 15.4 us, gate|up 21.2 -> 20.8 us at the 7B shape).  The other two
+    // producers measured no better with a second copy, so they keep the one.
+    if (r.pro == AF_PRO_RMSNORM && r.n <= RP_EV * THREADS)
+      produce_batched<1>(r, xs, sm, store_x, store_phase, store_stride, hist);
+    else
+      produce_batched<4>(r, xs, sm, store_x, store_phase, store_stride, hist);
+  }
+
+  template <int B>
+  static __device__ __forceinline__ void produce_batched(const af_row_src& r, unsigned short* xs, Smem& sm,
+                                                         bool store_x, int store_phase, int store_stride,
+                                                         unsigned* hist) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = r.n, nvec = n / RP_EV;
-    constexpr int B = 4;
     rp_half* xv = reinterpret_cast<rp_half*>(xs);
     const rp_half* src = reinterpret_cast<const rp_half*>(r.src);
     rp_half zero;
