@@ -78,7 +78,8 @@ const char* af_strerror(int status);
  * detected in validate mode; the GEMV then adds a repeated row twice.
  * AF_OPT_TUNE_*: launch-shape overrides for tuning sweeps, 0 = the built-in choice: lanes across
  * a tile (16, 32, 64), waves per workgroup (4, 8, 16), splits of the row list, workgroups
- * aimed at.  AF_OPT_MOE_ROUTER_KERNEL: 1 runs the router of af_decode_moe_layer as a launch of
+ * aimed at; AF_OPT_TUNE_ATTN_SPLITS: key splits of the attention launch (0 = one per 64 keys).
+ * AF_OPT_MOE_ROUTER_KERNEL: 1 runs the router of af_decode_moe_layer as a launch of
  * its own instead of inside the gate|up launch. */
 enum {
   AF_OPT_LAYER_KERNEL = 1,
@@ -87,7 +88,8 @@ enum {
   AF_OPT_TUNE_WAVES = 4,
   AF_OPT_TUNE_SPLIT = 5,
   AF_OPT_TUNE_WORKGROUPS = 6,
-  AF_OPT_MOE_ROUTER_KERNEL = 7
+  AF_OPT_MOE_ROUTER_KERNEL = 7,
+  AF_OPT_TUNE_ATTN_SPLITS = 8
 };
 int af_set_option(af_ctx* ctx, int option, int value);
 

@@ -25,6 +25,7 @@ AF_CALIB_BINS = 32768
 AF_NOALLOC_MAX_OUT, AF_ENOALLOC_LIMIT = 65536, -6
 AF_OPT_LAYER_KERNEL, AF_OPT_VALIDATE, AF_OPT_TUNE_LX, AF_OPT_TUNE_WAVES = 1, 2, 3, 4
 AF_OPT_TUNE_SPLIT, AF_OPT_TUNE_WORKGROUPS, AF_OPT_MOE_ROUTER_KERNEL = 5, 6, 7
+AF_OPT_TUNE_ATTN_SPLITS = 8
 AF_DEVERR_SPIN, AF_DEVERR_IDX = 1, 2
 
 EXPORTS = [

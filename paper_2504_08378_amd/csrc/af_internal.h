@@ -51,7 +51,7 @@ struct af_ctx {
   int use_layer_kernel;   // af_set_option(AF_OPT_LAYER_KERNEL, 1): one launch per layer
   int validate;           // af_set_option(AF_OPT_VALIDATE, 1): check caller index lists on the device
   // launch-shape overrides for tuning sweeps (af_set_option; 0 = the built-in heuristic)
-  int tune_lx, tune_nw, tune_split, tune_wgs, moe_router_kernel;
+  int tune_lx, tune_nw, tune_split, tune_wgs, moe_router_kernel, tune_attn_splits;
   int layer_kernel_state; // 0 not probed yet, 1 usable, -1 not usable on this device
 };
 

@@ -87,6 +87,9 @@ extern "C" int af_set_option(af_ctx* ctx, int option, int value) {
     case AF_OPT_MOE_ROUTER_KERNEL:
       ctx->moe_router_kernel = value ? 1 : 0;
       return AF_OK;
+    case AF_OPT_TUNE_ATTN_SPLITS:
+      ctx->tune_attn_splits = value;
+      return AF_OK;
     default:
       return AF_EINVAL;
   }

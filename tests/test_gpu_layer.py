@@ -531,3 +531,28 @@ def test_stack_selection_config_count_is_checked(ctx):
         assert e.value.status == -1
     st.run(to_dev(h), KV_LEN, KV_LEN, [sel] * 3)
     ctx.synchronize()
+
+
+@pytest.mark.parametrize("shape_name,splits", [("tiny_hd128", 3), ("tiny_gqa", 2), ("tiny_hd128", 0)])
+def test_attention_with_many_keys_per_split(ctx, shape_name, splits):
+    """Long caches cap the number of key splits, so a workgroup walks several batches of keys:
+    1500 keys in 3 (head width 128) or 2 (width 64) splits, and the default split choice."""
+    shape = S.MODEL_SHAPES[shape_name]
+    kv_len, kv_cap = 1500, 1504
+    layers, kv, h = _host_stack(shape, 1, seed=21, kv_len=kv_len, kv_cap=kv_cap)
+    ks = _ks(shape, 50)
+    st = _dev_stack(ctx, shape, layers, kv, kv_cap=kv_cap)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    ctx.set_option(B.AF_OPT_TUNE_ATTN_SPLITS, splits)
+    try:
+        st.layer(0, hin, hout, kv_len, kv_len, M.select_cfg(B.AF_SEL_TOPK, ks))
+        ctx.synchronize()
+    finally:
+        ctx.set_option(B.AF_OPT_TUNE_ATTN_SPLITS, 0)
+    taps = layer_taps(ctx, shape)
+    idx_gpu = [st.sets[0].fetch(p, ks[p]) for p in range(4)]
+    errs, own = teacher_forced_layer_errors(O, _ocfg(shape), layers[0], h, kv[0][0], kv[0][1], kv_len, kv_len,
+                                            taps, to_host(hout), idx_gpu, O.SelectCfg(O.SEL_TOPK, ks))
+    assert max(errs.values()) <= TOL, errs
+    for p in range(4):
+        assert np.array_equal(idx_gpu[p], own[p]), p
