@@ -23,6 +23,7 @@ struct af_ws_layout {
   size_t union_n;       // int32 [4]: its size per selection point
   size_t union_ranges;  // int32 [max_in rounded up to 256]: the union builder's per-range lists
   size_t union_range_cnt; // int32 [AF_MAX_N / 256]
+  size_t union_mask;    // uint32 [max_in]: per-channel token bits of the union builder, zero between calls
   size_t total;
   size_t partial_floats;
   size_t attn_floats;

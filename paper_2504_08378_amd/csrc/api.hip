@@ -31,6 +31,8 @@ af_ws_layout af_layout(int max_in, int max_out, int max_batch) {
   off = af_align(off + ((size_t)max_in + 256) * sizeof(int32_t));
   L.union_range_cnt = off;
   off = af_align(off + (AF_MAX_N / 256) * sizeof(int32_t));
+  L.union_mask = off;
+  off = af_align(off + (size_t)max_in * sizeof(uint32_t));
   L.total = off;
   return L;
 }
@@ -215,6 +217,10 @@ extern "C" int af_set_workspace(af_ctx* ctx, void* dev_ptr, size_t bytes, int ma
   // a fill kernel rather than a memset node, so the call is also safe under stream capture
   hipLaunchKernelGGL(fill_int_kernel, dim3((AF_N_TICKETS + 255) / 256), dim3(256), 0, ctx->stream,
                      (int*)(ctx->ws + ctx->lay.tickets), (int)AF_N_TICKETS, 0);
+  AF_LAUNCH_CHECK();
+  // the union builder's channel mask is all zero between calls
+  hipLaunchKernelGGL(fill_int_kernel, dim3((max_in + 255) / 256), dim3(256), 0, ctx->stream,
+                     (int*)(ctx->ws + ctx->lay.union_mask), max_in, 0);
   AF_LAUNCH_CHECK();
   return AF_OK;
 }

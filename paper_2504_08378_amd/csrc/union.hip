@@ -3,10 +3,10 @@
 //
 //   Y[b][o] = sum_{j in idx_b[b]} Wt[j][o] * X[b][j]
 //
-// Step 1 (two launches, one workgroup per 256 channels): scatter the B index lists into a
-// per-channel bit mask in LDS, write Xm[j][b] = X[b][j] if token b keeps channel j else 0
-// (fp16, 8 tokens per row = one 16-byte load in the GEMV), and emit the ascending union U
-// (each workgroup its own range, then moved into place behind the lower ranges).
+// Step 1 (three small launches): set bit b of channel j's word in a device-memory mask for every
+// entry j of token b's list; per 256 channels, turn the mask words into Xm[j][b] = X[b][j] if
+// token b keeps channel j else 0 (fp16, 8 tokens per row = one 16-byte load in the GEMV) and into
+// the range's part of the ascending union U; move the parts into place behind the lower ranges.
 // Step 2: the gathered GEMV of gemv_f16.hip over U with B accumulator sets per lane; every
 // weight row of the union is read once for all tokens.
 #include "af_internal.h"
@@ -20,6 +20,7 @@ struct UnionBuildParams {
   const half_t* X;         // [B][in]
   const int32_t* idx_b;    // [B][idx_stride], k entries used (or counts[b] of them)
   const int32_t* counts;   // per-token list lengths on the device, or null: k for every token
+  unsigned* mask;          // [in]: bit b of word j = token b keeps channel j; zero between calls
   int32_t* range_list;     // [ranges][UB_RANGE]: the union's channels of each range, ascending
   int32_t* range_cnt;      // [ranges]
   int32_t* union_idx;      // [in]
@@ -29,40 +30,41 @@ struct UnionBuildParams {
   int* tickets;            // the device error word lies behind them
 };
 
-// Builder, first launch: workgroup r owns the channels [r * UB_RANGE, (r + 1) * UB_RANGE).  It
-// reads every token's whole list (so a list that breaks the ascending-order precondition is
-// still handled entry by entry: what lies in the range is taken, what lies outside [0, in) is
-// dropped and reported), marks its channels in a bit mask in LDS, writes their masked,
-// transposed token values and leaves its part of the union, in ascending order, in range_list.
-__global__ __launch_bounds__(UB_THREADS) void union_scan_kernel(UnionBuildParams p) {
-  __shared__ unsigned s_mask[UB_RANGE];  // bit b = token b keeps the channel
+// Builder, first launch: every list entry is looked at once.  Grid (chunks of a list, tokens);
+// a thread takes up to four entries of its token's list and sets the token's bit in the
+// channel's word of a mask in device memory (all zero between calls).  An entry outside [0, in)
+// is dropped and reported.
+__global__ __launch_bounds__(UB_THREADS) void union_mark_kernel(UnionBuildParams p) {
+  const int b = blockIdx.y;
+  const int kb = p.counts ? min(max(p.counts[b], 0), p.k) : p.k;
+  const int32_t* list = p.idx_b + (size_t)b * p.idx_stride;
+  const int t0 = blockIdx.x * (4 * UB_THREADS) + threadIdx.x;
+  int j[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) j[u] = t0 + u * UB_THREADS < kb ? list[t0 + u * UB_THREADS] : -1;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    if (t0 + u * UB_THREADS >= kb) continue;
+    if ((unsigned)j[u] < (unsigned)p.in)
+      __hip_atomic_fetch_or(p.mask + j[u], 1u << b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      af_report_bad_index(p.tickets);  // broken precondition
+  }
+}
+
+// Builder, second launch: workgroup r owns the channels [r * UB_RANGE, (r + 1) * UB_RANGE): it
+// takes their mask words (and clears them for the next call), writes their masked, transposed
+// token values and leaves its part of the union, in ascending order, in range_list.
+__global__ __launch_bounds__(UB_RANGE) void union_gather_kernel(UnionBuildParams p) {
   __shared__ unsigned s_wtot[UB_RANGE / AF_WAVE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = blockIdx.x;
   const int c0 = r * UB_RANGE, cn = min(UB_RANGE, p.in - c0);
-  if (tid < UB_RANGE) s_mask[tid] = 0;
-  __syncthreads();
-  for (int b = 0; b < p.B; ++b) {
-    const int kb = p.counts ? min(max(p.counts[b], 0), p.k) : p.k;
-    const int32_t* list = p.idx_b + (size_t)b * p.idx_stride;
-    for (int t0 = tid; t0 < kb; t0 += 8 * UB_THREADS) {
-      int j[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) j[u] = t0 + u * UB_THREADS < kb ? list[t0 + u * UB_THREADS] : c0 - 1 - UB_RANGE;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        if ((unsigned)(j[u] - c0) < (unsigned)cn)
-          atomicOr(&s_mask[j[u] - c0], 1u << b);
-        else if (r == 0 && t0 + u * UB_THREADS < kb && (unsigned)j[u] >= (unsigned)p.in)
-          af_report_bad_index(p.tickets);  // broken precondition: the entry is dropped and reported
-      }
-    }
-  }
-  __syncthreads();
-  // one channel per thread (the first UB_RANGE threads have one)
   const bool in_range = tid < cn;
-  const unsigned m = in_range ? s_mask[tid] : 0u;
+  unsigned m = 0;
   if (in_range) {
+    m = __hip_atomic_load(p.mask + c0 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (m) __hip_atomic_store(p.mask + c0 + tid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     half8 v;
 #pragma unroll
     for (int b = 0; b < 8; ++b)
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(UB_THREADS) void union_scan_kernel(UnionBuildParams
   }
   const unsigned flag = m != 0;
   const unsigned inc = af_wave_incl_scan(flag);
-  if (lane == 63 && wave < UB_RANGE / AF_WAVE) s_wtot[wave] = inc;
+  if (lane == 63) s_wtot[wave] = inc;
   __syncthreads();
   unsigned base = 0, total = 0;
 #pragma unroll
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(UB_THREADS) void union_scan_kernel(UnionBuildParams
   if (tid == 0) p.range_cnt[r] = (int)total;
 }
 
-// Builder, second launch: workgroup r moves its range's channels to their place in the union
+// Builder, third launch: workgroup r moves its range's channels to their place in the union
 // (behind the channels of all lower ranges); workgroup 0 also writes the union's size.
 #define UP_THREADS 256
 __global__ __launch_bounds__(UP_THREADS) void union_place_kernel(UnionBuildParams p) {
@@ -297,7 +299,13 @@ int af_launch_union_f16(af_ctx* ctx, const af_union_args& u) {
   bp.idx_stride = u.idx_stride;
   bp.ranges = (in + UB_RANGE - 1) / UB_RANGE;
   bp.tickets = (int*)(ctx->ws + ctx->lay.tickets);
-  hipLaunchKernelGGL(union_scan_kernel, dim3(bp.ranges), dim3(UB_THREADS), 0, ctx->stream, bp);
+  bp.mask = (unsigned*)(ctx->ws + ctx->lay.union_mask);
+  if (k > 0) {
+    hipLaunchKernelGGL(union_mark_kernel, dim3((k + 4 * UB_THREADS - 1) / (4 * UB_THREADS), B), dim3(UB_THREADS), 0,
+                       ctx->stream, bp);
+    AF_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(union_gather_kernel, dim3(bp.ranges), dim3(UB_RANGE), 0, ctx->stream, bp);
   AF_LAUNCH_CHECK();
   hipLaunchKernelGGL(union_place_kernel, dim3(bp.ranges), dim3(UP_THREADS), 0, ctx->stream, bp);
   AF_LAUNCH_CHECK();
