@@ -106,8 +106,9 @@ int af_last_device_error(af_ctx* ctx, int* flags, int clear);
  * fused matrix) and max_batch tokens; 0 if an argument is invalid.
  * af_set_workspace() hands the buffer over for those limits (256-byte aligned, at least
  * af_workspace_bytes() long; the caller keeps ownership and must keep it alive while the
- * context uses it) and enqueues the clearing of its counter area on the stream.  Later
- * calls whose dimensions exceed the limits return AF_EWORKSPACE. */
+ * context uses it) and enqueues the clearing of its counter areas on the stream (they stay
+ * cleared between calls: a call that is not allowed to finish leaves them undefined, set the
+ * workspace again then).  Later calls whose dimensions exceed the limits return AF_EWORKSPACE. */
 size_t af_workspace_bytes(int max_in, int max_out, int max_batch);
 int af_set_workspace(af_ctx* ctx, void* dev_ptr, size_t bytes, int max_in, int max_out,
                      int max_batch);
