@@ -15,7 +15,9 @@ struct GemvParams {
   void* y;
   const half_t* residual;
   // The argument block stays within 248 bytes: launches of this kernel were measured 0.3-0.4 us
-  // slower once it grew past 256 bytes.  Hence the flag word.
+  // slower once it grew to 280 bytes (the launch itself does not care: near-empty kernels take
+  // the same time with 16 bytes or 1 KB of arguments; the cost was in this kernel's start-up).
+  // Hence the flag word.
   int out, ld, out_pad;
   int flags;  // GEMV_F_*
   int list_off;   // byte offset of the staged-row list in dynamic LDS (behind x)
