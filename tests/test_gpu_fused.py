@@ -70,6 +70,8 @@ def _topk_property(x16, idx, k):
     key = (np.asarray(x16).view(np.uint16) & 0x7FFF).astype(np.int64)
     assert len(idx) == k and np.all(np.diff(idx) > 0)
     sel = np.zeros(len(key), bool); sel[idx] = True
+    if k == 0 or k == len(key):
+        return
     lo, hi = key[sel].min(), key[~sel].max()
     assert lo >= hi
     if lo == hi:
@@ -233,3 +235,56 @@ def test_7b_shapes_fused_forms_sampled(ctx, name, out, n, producer):
     own = O.select_threshold(x_gpu, t)
     ref = O.sparse_gemv(W[rows], x_gpu, own)
     assert np.max(np.abs(y[rows] - ref)) <= 1e-4 * np.sqrt(np.mean(ref ** 2))
+
+
+def _random_cases(count, seed=2024):
+    """Seeded mix of operator shapes that reaches every launch-shape branch (narrow / medium / wide
+    tiles, one split and many), ragged sizes, every producer and both selection kinds."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        out = 8 * int(rng.integers(1, [40, 800, 1600, 3600][i % 4]))
+        n = 8 * int(rng.integers(1, min(2048, max(8, (3 << 20) // out))))   # the fused form takes in % 8 == 0
+        pro = ("none", "rmsnorm", "silumul")[int(rng.integers(0, 3))]
+        keep = float(rng.choice([0.05, 0.3, 0.5, 0.8, 1.0]))
+        cases.append((out, n, pro, keep, int(rng.integers(0, 3))))
+    return cases
+
+
+@pytest.mark.parametrize("out,n,pro,keep,form", _random_cases(28))
+def test_random_shapes_every_form(ctx, out, n, pro, keep, form):
+    """form 0: top-k with list, 1: threshold with list, 2: threshold by channel range."""
+    seed = out * 131 + n
+    W = S.weight_matrix(seed, out, n, "rand", out, n)
+    kw = {}
+    if pro == "rmsnorm":
+        src = S.activation(seed, S.channel_scales(seed, n, "rand"), "rand", 0)
+        g = S.norm_gain(seed, n, "rand")
+        kw = dict(producer=B.AF_PRO_RMSNORM, gain=to_dev(g), eps=1e-5)
+        x_ref = O.round_f16(O.rmsnorm(src, g, 1e-5))
+    elif pro == "silumul":
+        src = (S.activation(seed, S.channel_scales(seed, 2 * n, "rand"), "rand", 1).astype(np.float32)
+               * 0.3).astype(np.float16)
+        kw = dict(producer=B.AF_PRO_SILUMUL)
+        x_ref = O.round_f16(O.silu(src[:n]) * src[n:].astype(np.float64))
+    else:
+        src = S.activation(seed, S.channel_scales(seed, n, "rand"), "rand", 0)
+        x_ref = src
+    Wt = ctx.pack_inmajor_f16(to_dev(W)); sd = to_dev(src)
+    k = min(n, max(1, int(round(keep * n))))
+    if form == 0:
+        y, x_gpu, idx, c = _run(ctx, Wt, sd, n, sel_mode=B.AF_SEL_TOPK, k=k, y_kind=B.AF_F32, **kw)
+        _topk_property(x_gpu, idx, k)
+    else:
+        mags = np.sort(np.abs(x_ref.astype(np.float64)))
+        t = float(mags[n - k]) if k < n else 0.0
+        if form == 1:
+            y, x_gpu, idx, c = _run(ctx, Wt, sd, n, sel_mode=B.AF_SEL_THRESHOLD, t=t, y_kind=B.AF_F32, **kw)
+            assert np.array_equal(idx, O.select_threshold(x_gpu, t))
+        else:
+            y, x_gpu = _run_noidx(ctx, Wt, sd, n, t=t, **kw)
+            idx = O.select_threshold(x_gpu, t)
+    assert O.rel_err(x_gpu, x_ref) <= TOL
+    if pro == "none":
+        assert np.array_equal(x_gpu.view(np.uint16), x_ref.view(np.uint16))
+    assert O.rel_err(y, O.sparse_gemv(W, x_gpu, idx)) <= 1e-4

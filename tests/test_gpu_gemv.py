@@ -241,3 +241,25 @@ def test_index_precondition_is_reported_not_followed(ctx):
         assert ctx.last_device_error() == B.AF_DEVERR_IDX
     finally:
         ctx.set_option(B.AF_OPT_VALIDATE, 0)
+
+
+def _random_gemv_cases(count, seed=99):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        out = 8 * int(rng.integers(1, [40, 800, 1600, 3600][i % 4]))
+        n = int(rng.integers(1, min(16384, max(64, (24 << 20) // out))))
+        cases.append((out, n, max(1, int(n * float(rng.choice([0.02, 0.3, 0.5, 0.8, 1.0]))))))
+    return cases
+
+
+@pytest.mark.parametrize("out,n,k", _random_gemv_cases(20))
+def test_random_shapes_and_random_sets(ctx, out, n, k):
+    """Seeded shapes across the launch-shape branches with index sets drawn at random (any subset
+    is a valid argument, not only a top-k set)."""
+    W, x = _case(out, n, out * 3 + n)
+    idx = np.sort(np.random.default_rng(out + n).choice(n, size=k, replace=False)).astype(np.int32)
+    Wt = ctx.pack_inmajor_f16(to_dev(W))
+    y = ctx.sparse_gemv_f16(Wt, to_dev(x), to_dev(idx), y_kind=B.AF_F32)
+    ctx.synchronize()
+    assert O.rel_err(to_host(y), O.sparse_gemv(W, x, idx)) <= 1e-4

@@ -146,3 +146,33 @@ def test_unpack_is_the_inverse_of_pack_on_the_device(ctx, out, n, col0, ld):
     nib, s = O.quantize_q4_g32(W)
     assert np.array_equal(to_host(q).astype(np.int64), nib.astype(np.int64) - 8)
     assert np.array_equal(to_host(w).astype(np.float64), O.dequant_q4_g32(nib, s))
+
+
+def _random_q4_cases(count, seed=77):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        out = 32 * int(rng.integers(1, [10, 200, 400, 900][i % 4]))
+        n = 32 * int(rng.integers(1, min(512, max(2, (3 << 20) // (4 * out)))))
+        cases.append((out, n, max(1, int(n * float(rng.choice([0.05, 0.3, 0.5, 0.8, 1.0])))), i % 2))
+    return cases
+
+
+@pytest.mark.parametrize("out,n,k,cl", _random_q4_cases(16))
+def test_q4_random_shapes_both_layouts(ctx, out, n, k, cl):
+    """Seeded shapes across the launch-shape branches, in the row-major-group layout (cl = 0) and
+    the column-block layout (cl = 1)."""
+    W, x = _case(out, n, out * 7 + n)
+    idx = O.select_topk(x, k)
+    if cl:
+        nib, s = O.quantize_q4_cl(W)
+        packed, scales = ctx.pack_q4_cl(to_dev(W))
+        y = ctx.sparse_gemv_q4_cl(packed, scales, to_dev(x), to_dev(idx), y_kind=B.AF_F32)
+        ref = O.sparse_gemv_q4_cl(nib, s, x, idx)
+    else:
+        nib, s = O.quantize_q4_g32(W)
+        packed, scales = ctx.pack_q4_g32(to_dev(W))
+        y = ctx.sparse_gemv_q4(packed, scales, to_dev(x), to_dev(idx), y_kind=B.AF_F32)
+        ref = O.sparse_gemv_q4(nib, s, x, idx)
+    ctx.synchronize()
+    assert O.rel_err(to_host(y), ref) <= 1e-4
