@@ -35,6 +35,44 @@ struct AttnParams {
   float cs[64], sn[64];  // cos / sin of pos * theta^(-2i/HD), i < HD/2, formed in fp64 on the host
 };
 
+// Output element `c` of one head from the partial results of its KS key splits
+// ([KS][HD + 2]: running maximum, sum of weights, weighted values), summed in split order.  The
+// partials come from other XCDs, so every batch of loads is a trip to memory: sixteen splits go
+// out together (one trip for the usual split counts), and a running maximum rescales what
+// earlier batches summed.
+template <int HD>
+__device__ __forceinline__ float attn_combine(const float* base, const int KS, const int c) {
+  float M = -INFINITY, L = 0.f, v = 0.f;
+  for (int q0 = 0; q0 < KS; q0 += 16) {
+    float ms[16], ls[16], av[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const bool ok = q0 + u < KS;
+      const float* pp = base + (size_t)(q0 + u) * (HD + 2);
+      ms[u] = ok ? af_load_agent(pp) : -INFINITY;
+      ls[u] = ok ? af_load_agent(pp + 1) : 0.f;
+      av[u] = ok ? af_load_agent(pp + 2 + c) : 0.f;
+    }
+    float mb = M;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) mb = fmaxf(mb, ms[u]);
+    if (mb == -INFINITY) continue;  // nothing but empty splits so far
+    const float keep = (M == -INFINITY) ? 0.f : expf(M - mb);
+    L *= keep;
+    v *= keep;
+    M = mb;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if (ms[u] != -INFINITY) {  // an empty split has nothing to add
+        const float wgt = expf(ms[u] - M);
+        L += wgt * ls[u];
+        v += wgt * av[u];
+      }
+    }
+  }
+  return v / L;
+}
+
 // One (head, key split) workgroup of the decode attention.  cs / sn: the rotary table of the
 // token's position (kernel arguments for the single-token launch, LDS for the batched one).
 template <int HD>
@@ -223,40 +261,8 @@ __device__ __forceinline__ void attn_decode_body(const AttnParams& p, const floa
     af_prof_end(p.prof);
     return;
   }
-  // combine the splits in split order; loads go out eight splits at a time
   const float* base = p.part + (size_t)h * KS * (HD + 2);
-  if (tid < HD) {
-    float M = -INFINITY;
-    for (int q0 = 0; q0 < KS; q0 += 8) {
-      float ms[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        ms[u] = q0 + u < KS ? af_load_agent(base + (size_t)(q0 + u) * (HD + 2)) : -INFINITY;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) M = fmaxf(M, ms[u]);
-    }
-    float L = 0.f, v = 0.f;
-    for (int q0 = 0; q0 < KS; q0 += 8) {
-      float ms[8], ls[8], av[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const bool ok = q0 + u < KS;
-        const float* pp = base + (size_t)(q0 + u) * (HD + 2);
-        ms[u] = ok ? af_load_agent(pp) : -INFINITY;
-        ls[u] = ok ? af_load_agent(pp + 1) : 0.f;
-        av[u] = ok ? af_load_agent(pp + 2 + tid) : 0.f;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        if (ms[u] != -INFINITY) {  // an empty split has nothing to add
-          const float wgt = expf(ms[u] - M);
-          L += wgt * ls[u];
-          v += wgt * av[u];
-        }
-      }
-    }
-    p.out[(size_t)h * HD + tid] = (half_t)(v / L);
-  }
+  if (tid < HD) p.out[(size_t)h * HD + tid] = (half_t)attn_combine<HD>(base, KS, tid);
   if (tid == 0) af_ticket_reset(&p.tickets[h]);
   af_prof_end(p.prof);
 }
@@ -645,40 +651,8 @@ __device__ __forceinline__ bool attn_phase(const AttnParams& p, int h, int s, in
     __syncthreads();
     finisher = s_last != 0;
     if (finisher) {
-      // combine the splits in split order; loads go out eight splits at a time
       const float* base = p.part + (size_t)h * KS * (HD + 2);
-      if (tid < HD) {
-        float M = -INFINITY;
-        for (int q0 = 0; q0 < KS; q0 += 8) {
-          float ms[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            ms[u] = q0 + u < KS ? af_load_agent(base + (size_t)(q0 + u) * (HD + 2)) : -INFINITY;
-#pragma unroll
-          for (int u = 0; u < 8; ++u) M = fmaxf(M, ms[u]);
-        }
-        float Lsum = 0.f, v = 0.f;
-        for (int q0 = 0; q0 < KS; q0 += 8) {
-          float ms[8], ls[8], av[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const bool ok = q0 + u < KS;
-            const float* pp = base + (size_t)(q0 + u) * (HD + 2);
-            ms[u] = ok ? af_load_agent(pp) : -INFINITY;
-            ls[u] = ok ? af_load_agent(pp + 1) : 0.f;
-            av[u] = ok ? af_load_agent(pp + 2 + tid) : 0.f;
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            if (ms[u] != -INFINITY) {  // an empty split has nothing to add
-              const float wgt = expf(ms[u] - M);
-              Lsum += wgt * ls[u];
-              v += wgt * av[u];
-            }
-          }
-        }
-        s_out[tid] = __builtin_bit_cast(unsigned short, (half_t)(v / Lsum));
-      }
+      if (tid < HD) s_out[tid] = __builtin_bit_cast(unsigned short, (half_t)attn_combine<HD>(base, KS, tid));
       if (tid == 0) af_ticket_reset(&p.tickets[h]);
     }
   }
