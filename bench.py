@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # name and launch shape are repeated in the output so that a stale figure shows):
 # FETCH_SIZE KiB x fetch factor + WRITE_SIZE KiB x write factor, the factors being what the same
 # counters read for a plain 256 MiB device copy of known size.
-TRAFFIC = {("7b", "f16", 50): {"fetch_KiB": 44359.6, "fetch_factor": 2.000, "write_KiB": 409.8, "write_factor": 1.000,
+TRAFFIC = {("7b", "f16", 50): {"fetch_KiB": 44360.0, "fetch_factor": 2.000, "write_KiB": 409.8, "write_factor": 1.000,
                                "kernel": "gemv_f16_kernel<64, 8, 16, false, 5> grid 43x4",
                                "source": "profiles/gateup_7b_f16_sp50_pmc_traffic.md"}}
 
