@@ -171,6 +171,7 @@ struct af_union_args {
   const int32_t* counts;    // device int32[B] or null
   int32_t* union_idx;       // [in]
   int32_t* union_n;         // [1]
+  bool marked;              // the context's channel mask already holds the tokens' bits
   void* Y;                  // [B][out]
   int y_kind;
   const half_t* residual;   // [B][out] or null

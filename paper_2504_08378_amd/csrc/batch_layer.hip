@@ -6,9 +6,10 @@
 // single-token layer gives for that token alone.
 //
 // Per selection point: one launch of B workgroups builds each token's operator input (RMSNorm,
-// copy, or SiLU(gate)*up) and selects on it (the front end of row_prologue.h, one workgroup per
-// token), one launch builds the union, one launch streams the union's weight rows for all
-// tokens.  Attention is one launch over (head, key split, token); each token has its own cache,
+// copy, or SiLU(gate)*up), selects on it (the front end of row_prologue.h, one workgroup per
+// token) and sets the token's bit in the channel mask for every channel it keeps; one launch
+// turns the mask into the union and the masked token values; one launch streams the union's
+// weight rows for all tokens.  Attention is one launch over (head, key split, token); each token has its own cache,
 // length and position.
 #include <math.h>
 
@@ -22,6 +23,7 @@ struct BatchSelectParams {
   long long src_stride;  // elements between the tokens' sources
   long long x_stride;    // ... their produced inputs (x_out)
   long long idx_stride;  // ... their index lists
+  unsigned* mask;        // [n] channel mask of the union builder (bit b: token b keeps the channel)
 };
 
 __global__ __launch_bounds__(BS_THREADS) void batch_select_kernel(BatchSelectParams p) {
@@ -39,6 +41,20 @@ __global__ __launch_bounds__(BS_THREADS) void batch_select_kernel(BatchSelectPar
   RP::produce(r, xs, s_rp, true, 0, 1, topk ? s_scratch : nullptr);
   int nidx;
   RP::select_split(r, xs, s_scratch, s_rp, nullptr, 1, 0, true, true, &nidx, topk);
+  // the list just written (its stores were waited for at the barrier that ends the selection),
+  // read back past the CU's cache: every kept channel gets this token's bit
+  for (int i0 = threadIdx.x; i0 < nidx; i0 += 8 * BS_THREADS) {
+    int j[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * BS_THREADS;
+      j[u] = i < nidx ? __hip_atomic_load(r.idx_out + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if ((unsigned)j[u] < (unsigned)r.n)
+        __hip_atomic_fetch_or(p.mask + j[u], 1u << b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 static int launch_batch_select(af_ctx* ctx, int B, int producer, const half_t* src, long long src_stride,
@@ -66,6 +82,7 @@ static int launch_batch_select(af_ctx* ctx, int B, int producer, const half_t* s
   p.src_stride = src_stride;
   p.x_stride = n;
   p.idx_stride = n;
+  p.mask = (unsigned*)(ctx->ws + ctx->lay.union_mask);
   const size_t lds = af_align((size_t)n * 2, 16);
   hipLaunchKernelGGL(batch_select_kernel, dim3(B), dim3(BS_THREADS), lds, ctx->stream, p);
   AF_LAUNCH_CHECK();
@@ -135,6 +152,7 @@ extern "C" int af_decode_layer_batch(af_ctx* ctx, const af_layer_cfg* cfg, const
     u.counts = sel->mode == AF_SEL_TOPK ? nullptr : sets->count[p];
     u.union_idx = un_idx;
     u.union_n = un_n + p;
+    u.marked = true;        // by the selection launch
     u.Y = Y;
     u.y_kind = AF_F16;
     u.residual = residual;

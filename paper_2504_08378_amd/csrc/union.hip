@@ -4,7 +4,8 @@
 //   Y[b][o] = sum_{j in idx_b[b]} Wt[j][o] * X[b][j]
 //
 // Step 1 (three small launches): set bit b of channel j's word in a device-memory mask for every
-// entry j of token b's list; per 256 channels, turn the mask words into Xm[j][b] = X[b][j] if
+// entry j of token b's list (the batched decoder layer does this inside its selection launch
+// instead); per 256 channels, turn the mask words into Xm[j][b] = X[b][j] if
 // token b keeps channel j else 0 (fp16, 8 tokens per row = one 16-byte load in the GEMV) and into
 // the range's part of the ascending union U; move the parts into place behind the lower ranges.
 // Step 2: the gathered GEMV of gemv_f16.hip over U with B accumulator sets per lane; every
@@ -300,7 +301,7 @@ int af_launch_union_f16(af_ctx* ctx, const af_union_args& u) {
   bp.ranges = (in + UB_RANGE - 1) / UB_RANGE;
   bp.tickets = (int*)(ctx->ws + ctx->lay.tickets);
   bp.mask = (unsigned*)(ctx->ws + ctx->lay.union_mask);
-  if (k > 0) {
+  if (k > 0 && !u.marked) {
     hipLaunchKernelGGL(union_mark_kernel, dim3((k + 4 * UB_THREADS - 1) / (4 * UB_THREADS), B), dim3(UB_THREADS), 0,
                        ctx->stream, bp);
     AF_LAUNCH_CHECK();
