@@ -556,3 +556,54 @@ def test_attention_with_many_keys_per_split(ctx, shape_name, splits):
     assert max(errs.values()) <= TOL, errs
     for p in range(4):
         assert np.array_equal(idx_gpu[p], own[p]), p
+
+
+def _random_layer_cases(count, seed=7):
+    """Seeded decoder-layer shapes off the beaten path: model widths that are no power of two,
+    query width different from the model width, 1 / 2 / 4 query heads per key head, both head
+    widths, any cache length, every weight format and both selection rules."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        hd = int(rng.choice([64, 128]))
+        n_kv = int(rng.choice([1, 2, 4]))
+        nh = n_kv * int(rng.choice([1, 2, 4]))
+        d = 32 * int(rng.integers(2, 24))
+        f = 32 * int(rng.integers(3, 60))
+        cases.append((i, d, nh, n_kv, hd, f, int(rng.integers(0, 200)), int(rng.choice([0, 30, 50, 70, 90])),
+                      str(rng.choice(["topk", "threshold"])), str(rng.choice(["f16", "q4", "q4cl"]))))
+    return cases
+
+
+@pytest.mark.parametrize("i,d,nh,n_kv,hd,f,kv_len,sp,rule,fmt", _random_layer_cases(16))
+def test_random_layer_shapes_stage_by_stage(ctx, i, d, nh, n_kv, hd, f, kv_len, sp, rule, fmt):
+    shape = S.ModelShape(f"rand{i}", 1, d, nh, n_kv, hd, f)
+    kv_cap = kv_len + 8
+    layers, kv, h = _host_stack(shape, 1, seed=100 + i, kv_len=kv_len, kv_cap=kv_cap)
+    kind = {"f16": B.AF_W_F16, "q4": B.AF_W_Q4G32, "q4cl": B.AF_W_Q4CL}[fmt]
+    if fmt == "f16":
+        wq, q4 = layers[0], False
+    elif fmt == "q4":
+        wq, q4 = {k: (O.quantize_q4_g32(v) if k.startswith("W") else v) for k, v in layers[0].items()}, True
+    else:
+        wq, q4 = _fused_cl(layers[0]), "cl"
+    ks = _ks(shape, sp)
+    osel = O.SelectCfg(O.SEL_TOPK, ks)
+    gsel = M.select_cfg(B.AF_SEL_TOPK, ks)
+    if rule == "threshold":   # thresholds near the same keep rate, from the oracle's own activations
+        tr = O.decode_layer(_ocfg(shape), wq, h, kv[0][0].copy(), kv[0][1].copy(), kv_len, kv_len, osel,
+                            weights_q4=q4)
+        ts = tuple(float(np.float32(np.sort(np.abs(tr.x[p].astype(np.float64)))[len(tr.x[p]) - max(ks[p], 1)]))
+                   for p in range(4))
+        osel = O.SelectCfg(O.SEL_THRESHOLD, t=ts)
+        gsel = M.select_cfg(B.AF_SEL_THRESHOLD, t=ts)
+    st = _dev_stack(ctx, shape, layers, kv, kv_cap=kv_cap, kind=kind)
+    hin = to_dev(h); hout = torch.zeros_like(hin)
+    st.layer(0, hin, hout, kv_len, kv_len, gsel)
+    ctx.synchronize()
+    got = [st.sets[0].fetch(p, ks[p] if rule == "topk" else None) for p in range(4)]
+    errs, own = teacher_forced_layer_errors(O, _ocfg(shape), wq, h, kv[0][0], kv[0][1], kv_len, kv_len,
+                                            layer_taps(ctx, shape), to_host(hout), got, osel, weights_q4=q4)
+    for p in range(4):   # the sets are the definition applied to the GPU's own inputs
+        assert np.array_equal(got[p], own[p]), p
+    assert max(errs.values()) <= TOL, errs
