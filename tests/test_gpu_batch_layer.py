@@ -170,3 +170,37 @@ def test_batch_layer_70b_shape(ctx, Bt):
     ks = tuple(O.keep_count(n, 50) for n in _widths(shape))
     res = _run_batch(ctx, shape, w, H, caches, kv_lens, kv_cap, M.select_cfg(B.AF_SEL_TOPK, ks))
     _check_tokens(ctx, shape, w, H, caches, kv_lens, O.SelectCfg(O.SEL_TOPK, ks), *res, free_running=False)
+
+
+def _random_batch_cases(count, seed=11):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        hd = int(rng.choice([64, 128]))
+        n_kv = int(rng.choice([1, 2, 4]))
+        nh = n_kv * int(rng.choice([1, 2, 4]))
+        cases.append((i, 32 * int(rng.integers(2, 24)), nh, n_kv, hd, 32 * int(rng.integers(3, 60)),
+                      int(rng.integers(1, 9)), int(rng.choice([0, 30, 50, 70, 90])), str(rng.choice(["topk", "threshold"]))))
+    return cases
+
+
+@pytest.mark.parametrize("i,d,nh,n_kv,hd,f,Bt,sp,rule", _random_batch_cases(10))
+def test_batch_layer_random_shapes(ctx, i, d, nh, n_kv, hd, f, Bt, sp, rule):
+    """Seeded shapes off the beaten path (odd widths, query width != model width, any batch size
+    from 1 to 8, caches of unrelated lengths), every token stage by stage."""
+    shape = S.ModelShape(f"brand{i}", 1, d, nh, n_kv, hd, f)
+    rng = np.random.default_rng(1000 + i)
+    kv_cap = 160
+    kv_lens = [int(v) for v in rng.integers(0, kv_cap - 1, size=Bt)]
+    w, H, caches = _inputs(shape, Bt, kv_cap, kv_lens, seed=200 + i)
+    ks = tuple(O.keep_count(n, sp) for n in _widths(shape))
+    if rule == "topk":
+        gsel, osel = M.select_cfg(B.AF_SEL_TOPK, ks), O.SelectCfg(O.SEL_TOPK, ks)
+    else:   # thresholds near the same keep rate, from the first token's activations in the oracle
+        K, V = caches[0]
+        tr = O.decode_layer(_ocfg(shape), w, H[0], K.copy(), V.copy(), kv_lens[0], kv_lens[0], O.SelectCfg(O.SEL_TOPK, ks))
+        ts = tuple(float(np.float32(np.sort(np.abs(tr.x[p].astype(np.float64)))[len(tr.x[p]) - max(ks[p], 1)]))
+                   for p in range(4))
+        gsel, osel = M.select_cfg(B.AF_SEL_THRESHOLD, t=ts), O.SelectCfg(O.SEL_THRESHOLD, t=ts)
+    res = _run_batch(ctx, shape, w, H, caches, kv_lens, kv_cap, gsel)
+    _check_tokens(ctx, shape, w, H, caches, kv_lens, osel, *res, free_running=False)
